@@ -1,0 +1,165 @@
+/*
+ * pe.h -- C ABI of libpe: the data-parallel hot path of PagedEviction on one AMD MI355X (gfx950).
+ *
+ * The path has three parts over a paged KV cache (Sec. 2.4: fixed-size blocks of B tokens, a block
+ * table that maps logical to physical blocks):
+ *   1. attention-free importance scores from the cached K/V (Alg. 1), one per block;
+ *   2. structured eviction: token-level pruning of the prompt to the budget C before it is split
+ *      into pages (Alg. 2), then, during decode, dropping the lowest-scoring block of a row whenever
+ *      its newest block has filled, and compacting the block table (Alg. 3);
+ *   3. the single-query paged attention that reads what is left (Eq. 1; Alg. 3 "PagedAttention").
+ *
+ * Granularity: every decision is taken per ROW = one (sequence, KV head).  A row owns one row of the
+ * block table and its own pages; a page holds B x D elements of K (and a sibling page of V, same
+ * physical index in v_pool) of ONE KV head.  Layers are independent: for (1), (2) a caller may fold
+ * layers into the sequence dimension.
+ *
+ * Conventions that hold for every call below:
+ *   - Every pointer except `desc` is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees or synchronises; `stream` is a hipStream_t passed as void* (NULL = the null
+ *     stream).  A call enqueues its kernels on `stream` and returns a host-side status at once.
+ *   - Tensors are dense, row-major, in the shapes given; K/V/q/out element type is desc->dtype
+ *     (PE_F32: IEEE binary32, PE_BF16: bfloat16); tables and lengths are int32.
+ *   - Pools: [num_phys_blocks][block_size][head_dim]; page p starts at element p*B*D.
+ *   - block_table: [num_seqs][num_kv_heads][max_blocks]; entry j of a row is the physical page of its
+ *     logical page j; entries at and beyond ceil(len/B) are -1.  seq_lens: [num_seqs] cached tokens
+ *     (the same for all KV heads of a sequence).
+ *   - Host-detectable misuse (NULL pointer, unsupported shape, budget not a positive multiple of B,
+ *     workspace too small or misaligned) returns a negative status and launches nothing.  A failed
+ *     launch returns PE_ERR_HIP.  What the host cannot see without a sync is a CALLER PRECONDITION:
+ *     every used table entry lies in [0, num_phys_blocks), rows do not share pages,
+ *     seq_lens[s] <= max_blocks*B, and all K/V values are finite.
+ *   - Workspaces must be 256-byte aligned.  Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef PE_H_
+#define PE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PE_OK = 0,
+  PE_ERR_INVALID_ARG = -1, /* NULL pointer, inconsistent or non-positive sizes, bad budget */
+  PE_ERR_UNSUPPORTED = -2, /* a shape the kernels are not built for (see pe_cache_desc) */
+  PE_ERR_WORKSPACE = -3,   /* workspace NULL, misaligned or smaller than pe_workspace_bytes() */
+  PE_ERR_HIP = -4          /* the HIP runtime refused a launch */
+} pe_status;
+
+typedef enum { PE_F32 = 0, PE_BF16 = 1 } pe_dtype;
+
+typedef enum {
+  PE_OP_SCORE_BLOCKS = 0,
+  PE_OP_PREFILL_PRUNE = 1,
+  PE_OP_EVICT_BLOCKS = 2,
+  PE_OP_PAGED_DECODE = 3
+} pe_op;
+
+typedef struct pe_cache_desc {
+  int32_t dtype;           /* pe_dtype of q, pools, k_in/v_in, out */
+  int32_t num_seqs;        /* S >= 1 */
+  int32_t num_kv_heads;    /* Hk >= 1 */
+  int32_t num_q_heads;     /* Hq, a multiple of Hk with Hq/Hk <= 8; q head h reads KV head h/(Hq/Hk) */
+  int32_t head_dim;        /* D: 64 or 128 */
+  int32_t block_size;      /* B: 16 or 32 tokens per page */
+  int32_t max_blocks;      /* row stride of block_table and of the score array */
+  int64_t num_phys_blocks; /* P: pages in each pool */
+} pe_cache_desc;
+
+/* Bytes of device workspace `op` needs for `desc`.  `total_tokens` is the packed prompt length
+ * (sum of L) for PE_OP_PREFILL_PRUNE and ignored otherwise.  Returns 0 for ops that need none and
+ * for an invalid desc. */
+size_t pe_workspace_bytes(int op, const pe_cache_desc* desc, int64_t total_tokens);
+
+/* Static string for a pe_status value. */
+const char* pe_status_string(int status);
+
+/* ABI version: major*10000 + minor*100 + patch. */
+int pe_version(void);
+
+/* Tuning knobs (host side, process wide, not thread safe).  key PE_OPT_DECODE_SPLITS: number of
+ * splits of a row in pe_paged_decode (0 = choose from the shape).  Returns PE_OK or
+ * PE_ERR_INVALID_ARG.  pe_workspace_bytes() follows the current setting. */
+enum { PE_OPT_DECODE_SPLITS = 0, PE_OPT_DECODE_XCD_MAP = 1, PE_OPT_COUNT_ = 2 };
+int pe_set_option(int key, int value);
+int pe_get_option(int key);
+
+/*
+ * (1) Block scores -- Alg. 1 (block mode), used by Alg. 3 "Compute Score of Page i"; Sec. 4.3.
+ *     For every row and every FULL page j < seq_lens[s]/B:
+ *        scores_out[s][hk][j] = (1/B) * sum over the page's B tokens of ||V_i||_2 / ||K_i||_2,
+ *     accumulated in fp64 and rounded once to fp32.  Every other entry (partial tail page, unused)
+ *     is +INF.  A token with ||V|| = 0 contributes 0; otherwise ||K|| = 0 contributes +INF.
+ *     scores_out: [S][Hk][max_blocks] fp32, fully overwritten.  Reads pools/table/lens only.
+ *     workspace: none needed (may be NULL / 0).
+ */
+int pe_score_blocks(const pe_cache_desc* desc, const void* k_pool, const void* v_pool,
+                    const int32_t* block_table, const int32_t* seq_lens, float* scores_out, void* workspace,
+                    size_t workspace_bytes, void* stream);
+
+/*
+ * (2) Prefill prune -- Alg. 2, the steps after the prompt's own attention: score every prompt token
+ *     (S_i = ||V_i||_2/||K_i||_2, fp64, rounded once to fp32), evict the E = max(0, L - C) tokens that
+ *     come first in the order (score ascending, index ascending), and write the survivors, in their
+ *     original order, into pages: kept token number i of row (s, hk) goes to page
+ *     block_table[s][hk][i / B], slot i % B.  seq_lens_out[s] = min(L_s, C).
+ *     k_in, v_in: packed prompt [total_tokens][Hk][D] (the layout before paging), read only.
+ *     cu_seqlens: [S+1] int32 prefix sums of the prompt lengths, cu_seqlens[S] == total_tokens.
+ *     max_seqlen: an upper bound on every L_s (host value, sizes the launch).
+ *     budget_tokens: C, a positive multiple of B.
+ *     block_table is an INPUT: the caller has put ceil(min(L_s, C)/B) distinct physical pages in each
+ *     row.  Slots of the tail page past the kept count are left untouched.
+ *     kept_idx_out: NULL, or [S][Hk][budget_tokens] int32 that receives the in-sequence indices of the
+ *     kept tokens in ascending order, -1 padded.
+ *     workspace: pe_workspace_bytes(PE_OP_PREFILL_PRUNE, desc, total_tokens).
+ */
+int pe_prefill_prune(const pe_cache_desc* desc, const void* k_in, const void* v_in, const int32_t* cu_seqlens,
+                     int64_t total_tokens, int32_t max_seqlen, int32_t budget_tokens, void* k_pool,
+                     void* v_pool, const int32_t* block_table, int32_t* seq_lens_out, int32_t* kept_idx_out,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * (3) Evict -- Alg. 3, "Evict One page with the lowest score" and "Update the KV Cache Block Table".
+ *     A sequence s triggers when seq_lens[s] > 0, seq_lens[s] % B == 0 and seq_lens[s] >= budget_tokens
+ *     (its newest page has just filled and it is at budget).  Each of its rows removes logical page
+ *     j* = the first index that attains min_j scores[s][hk][j] over j < seq_lens[s]/B (ties: lowest
+ *     index), shifts the later entries left by one (order kept) and writes -1 into the vacated tail
+ *     entry.  evicted_logical_out / freed_phys_out [S][Hk] receive j* / the physical page that was
+ *     removed, or -1 for rows that did not evict.  seq_lens[s] -= B, once per triggering sequence.
+ *     Exactly one page per row per call.  scores: [S][Hk][max_blocks] fp32 (e.g. from (1)); compared
+ *     as fp32 values.  block_table and seq_lens are updated in place.
+ */
+int pe_evict_blocks(const pe_cache_desc* desc, const float* scores, int32_t* block_table, int32_t* seq_lens,
+                    int32_t budget_tokens, int32_t* evicted_logical_out, int32_t* freed_phys_out, void* stream);
+
+/*
+ * (4) Paged decode attention -- Eq. 1 for one new query per sequence; Alg. 3 "PagedAttention(Q,K,V)".
+ *     out[s][h][:] = sum_t softmax_t(softmax_scale * <q[s][h], K_t>) V_t over the seq_lens[s] tokens of
+ *     row (s, h / (Hq/Hk)), token t being slot t % B of page block_table[s][hk][t / B].
+ *     fp32 accumulation, output rounded to desc->dtype.  seq_lens[s] == 0 gives zeros.
+ *     q, out: [S][Hq][D].  workspace: pe_workspace_bytes(PE_OP_PAGED_DECODE, desc, 0) (split partials).
+ */
+int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool, const void* v_pool,
+                    const int32_t* block_table, const int32_t* seq_lens, float softmax_scale, void* out,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Harness convenience (not part of the paper's method): the step between (3) and (4) in a decode
+ * iteration.  Writes the new token's K/V row of every (s, hk) into slot seq_lens[s] % B of the tail
+ * page.  When seq_lens[s] % B == 0 a new page is linked in at logical index seq_lens[s]/B: the page
+ * the row freed in the eviction just before (freed_phys[s][hk] >= 0; consumed, reset to -1), else
+ * spare[s][hk][spare_used[s][hk]++].  Then seq_lens[s] += 1.
+ * new_k, new_v: [S][Hk][D].  spare: [S][Hk][n_spare] int32.  spare_used, freed_phys: [S][Hk] int32,
+ * updated in place.  Preconditions: seq_lens[s] < max_blocks*B; the spare list is not exhausted.
+ */
+int pe_append_kv(const pe_cache_desc* desc, const void* new_k, const void* new_v, void* k_pool, void* v_pool,
+                 int32_t* block_table, int32_t* seq_lens, int32_t* freed_phys, const int32_t* spare,
+                 int32_t* spare_used, int32_t n_spare, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PE_H_ */
