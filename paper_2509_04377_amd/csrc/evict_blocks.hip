@@ -1,0 +1,162 @@
+// Decode-time eviction (Alg. 3: "Evict One page with the lowest score", "Update the KV Cache Block
+// Table") and the harness append step that follows it in a decode iteration.
+//
+// evict: one workgroup per sequence, one wave per (sequence, KV head) row at a time.  The wave finds
+// argmin_j (score_j, j) over the row's full pages with a lane-strided scan and a lexicographic
+// wave reduction (ties: lowest logical index), then shifts the table entries behind the evicted one
+// left by one, 64 entries per pass.  seq_lens[s] is read by every wave before the barrier and
+// written once after it.
+#include "pe_device.h"
+#include "pe_launch.h"
+
+namespace pe {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+
+template <int M>
+__device__ __forceinline__ void min_step(float& sc, int& idx) {
+  const float osc = lane_xor_f32<M>(sc);
+  const int oidx = lane_xor_i32<M>(idx);
+  if (osc < sc || (osc == sc && oidx < idx)) {
+    sc = osc;
+    idx = oidx;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* __restrict__ scores,
+                                                                int32_t* __restrict__ block_table,
+                                                                int32_t* __restrict__ seq_lens,
+                                                                int32_t* __restrict__ evicted_logical,
+                                                                int32_t* __restrict__ freed_phys, int num_kv_heads,
+                                                                int block_size, int max_blocks, int budget) {
+  const int s = (int)blockIdx.x;
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+  const int len = seq_lens[s];
+  const bool trigger = len > 0 && (len % block_size) == 0 && len >= budget;
+  const int n = len / block_size;
+
+  for (int h = wave; h < num_kv_heads; h += kWaves) {
+    const int64_t row = (int64_t)s * num_kv_heads + h;
+    if (!trigger) {
+      if (lane == 0) {
+        evicted_logical[row] = -1;
+        freed_phys[row] = -1;
+      }
+      continue;
+    }
+    const float* sc_row = scores + row * max_blocks;
+    int32_t* bt = block_table + row * max_blocks;
+    float best = __builtin_inff();
+    int best_j = 0x7fffffff;
+    for (int j = lane; j < n; j += kWave) {
+      const float v = sc_row[j];
+      if (v < best || (v == best && j < best_j)) {
+        best = v;
+        best_j = j;
+      }
+    }
+    min_step<1>(best, best_j);
+    min_step<2>(best, best_j);
+    min_step<4>(best, best_j);
+    min_step<8>(best, best_j);
+    min_step<16>(best, best_j);
+    min_step<32>(best, best_j);
+    const int jstar = __builtin_amdgcn_readfirstlane(best_j);
+    const int freed = bt[jstar];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_s_waitcnt(0);  // the evicted entry has been read before any store below is issued
+    // stable left shift of entries jstar+1 .. n-1; each pass loads its 64 sources before it stores,
+    // and a pass only stores to positions that later passes do not read.
+    for (int base = (jstar / kWave) * kWave; base < n; base += kWave) {
+      const int j = base + lane;
+      const bool move = j >= jstar && j < n;
+      int32_t v = -1;
+      if (move && j + 1 < n) v = bt[j + 1];
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_s_waitcnt(0);  // all 64 sources are in registers before the stores are issued
+      if (move) bt[j] = v;
+    }
+    if (lane == 0) {
+      evicted_logical[row] = jstar;
+      freed_phys[row] = freed;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0 && trigger) seq_lens[s] = len - block_size;
+}
+
+// Append: one workgroup per sequence.  Phase 1 links a new page into each row when the tail page is
+// full; phase 2 copies the new K/V rows with 16-byte lane accesses.
+template <int VEC_PER_ROW>
+__global__ __launch_bounds__(kThreads) void append_kv_kernel(const uint4* __restrict__ new_k,
+                                                             const uint4* __restrict__ new_v,
+                                                             uint4* __restrict__ k_pool, uint4* __restrict__ v_pool,
+                                                             int32_t* __restrict__ block_table,
+                                                             int32_t* __restrict__ seq_lens,
+                                                             int32_t* __restrict__ freed_phys,
+                                                             const int32_t* __restrict__ spare,
+                                                             int32_t* __restrict__ spare_used, int n_spare,
+                                                             int num_kv_heads, int block_size, int max_blocks) {
+  const int s = (int)blockIdx.x;
+  const int len = seq_lens[s];
+  const int slot = len % block_size;
+  const int jb = len / block_size;
+  if (jb >= max_blocks) return;  // caller precondition violated: leave everything untouched
+  if (slot == 0) {
+    for (int h = (int)threadIdx.x; h < num_kv_heads; h += kThreads) {
+      const int64_t row = (int64_t)s * num_kv_heads + h;
+      int32_t page = freed_phys[row];
+      if (page >= 0) {
+        freed_phys[row] = -1;
+      } else {
+        const int used = spare_used[row];
+        page = used < n_spare ? spare[row * n_spare + used] : -1;
+        spare_used[row] = used + 1;
+      }
+      block_table[row * max_blocks + jb] = page;
+    }
+  }
+  __syncthreads();
+  for (int idx = (int)threadIdx.x; idx < num_kv_heads * VEC_PER_ROW; idx += kThreads) {
+    const int h = idx / VEC_PER_ROW, u = idx % VEC_PER_ROW;
+    const int64_t row = (int64_t)s * num_kv_heads + h;
+    const int32_t page = block_table[row * max_blocks + jb];
+    if (page < 0) continue;  // spare list exhausted (precondition violated): drop the token
+    const int64_t dst = ((int64_t)page * block_size + slot) * VEC_PER_ROW + u;
+    k_pool[dst] = new_k[row * VEC_PER_ROW + u];
+    v_pool[dst] = new_v[row * VEC_PER_ROW + u];
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) seq_lens[s] = len + 1;
+}
+
+}  // namespace
+
+hipError_t launch_evict_blocks(const EvictArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL(evict_blocks_kernel, dim3((unsigned)a.num_seqs), dim3(kThreads), 0, stream, a.scores,
+                     a.block_table, a.seq_lens, a.evicted_logical, a.freed_phys, a.num_kv_heads, a.block_size,
+                     a.max_blocks, a.budget);
+  return hipGetLastError();
+}
+
+hipError_t launch_append_kv(const AppendArgs& a, hipStream_t stream) {
+  const int vec_per_row = a.head_dim * (a.is_bf16 ? 2 : 4) / 16;
+#define PE_APPEND(V)                                                                                          \
+  if (vec_per_row == V) {                                                                                     \
+    hipLaunchKernelGGL((append_kv_kernel<V>), dim3((unsigned)a.num_seqs), dim3(kThreads), 0, stream,          \
+                       (const uint4*)a.new_k, (const uint4*)a.new_v, (uint4*)a.k_pool, (uint4*)a.v_pool,      \
+                       a.block_table, a.seq_lens, a.freed_phys, a.spare, a.spare_used, a.n_spare,             \
+                       a.num_kv_heads, a.block_size, a.max_blocks);                                           \
+    return hipGetLastError();                                                                                 \
+  }
+  PE_APPEND(8)
+  PE_APPEND(16)
+  PE_APPEND(32)
+#undef PE_APPEND
+  return hipErrorInvalidValue;
+}
+
+}  // namespace pe

@@ -1,0 +1,441 @@
+// Paged decode attention (Eq. 1 for one new query per sequence; Alg. 3 "PagedAttention(Q,K,V)").
+//
+// A workgroup owns one split of one (sequence, KV head) row: a contiguous range of tiles of the row's
+// tokens.  Each of its four waves walks tiles with a two-deep register pipeline.  Inside a tile every
+// lane holds 16 bytes of four K rows and four V rows (consecutive lanes = consecutive addresses, so
+// each wave-load is 1 KiB of one page, found through the block table with scalar loads).
+//
+//   QK:  each lane multiplies its K slice with the matching slice of all G query heads that share this
+//        KV head; the partial dots are reduced over the lanes of a token row with a reduce-scatter over
+//        heads, so that afterwards each lane owns the logit of ONE (token, head) pair;
+//   softmax: online, state (m, l) kept per lane for its head and its own stream of tokens
+//        (base-2 exponentials; the scale carries log2 e);
+//   PV:  the lane's probability is broadcast inside its group of lanes and multiplies the V slice
+//        into per-head fp32 accumulators.
+//
+// At the end the (wave, token-stream) partial states are merged through LDS; with one split the
+// workgroup writes the normalised output, otherwise it writes (acc, m, l) partials that
+// paged_decode_reduce_kernel merges.
+#include "pe_device.h"
+#include "pe_launch.h"
+
+namespace pe {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kLoadsPerTile = 4;
+constexpr float kNegInf = -__builtin_inff();
+
+constexpr int next_pow2(int x) { return x <= 1 ? 1 : 2 * next_pow2((x + 1) / 2); }
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+// The 16 bytes of one query head that face a lane's 16-byte K slice.
+template <typename T>
+struct QSlice;
+template <>
+struct QSlice<float> {
+  float v[4];
+  __device__ __forceinline__ void load(const float* p) {
+    const uint4 r = *reinterpret_cast<const uint4*>(p);
+    v[0] = __uint_as_float(r.x);
+    v[1] = __uint_as_float(r.y);
+    v[2] = __uint_as_float(r.z);
+    v[3] = __uint_as_float(r.w);
+  }
+  __device__ __forceinline__ void zero() { v[0] = v[1] = v[2] = v[3] = 0.f; }
+  __device__ __forceinline__ float dot(const uint4& k) const {
+    float a = __uint_as_float(k.x) * v[0];
+    a = fmaf(__uint_as_float(k.y), v[1], a);
+    a = fmaf(__uint_as_float(k.z), v[2], a);
+    a = fmaf(__uint_as_float(k.w), v[3], a);
+    return a;
+  }
+};
+template <>
+struct QSlice<bf16_t> {
+  uint32_t v[4];  // 8 bf16, packed as in memory
+  __device__ __forceinline__ void load(const bf16_t* p) {
+    const uint4 r = *reinterpret_cast<const uint4*>(p);
+    v[0] = r.x;
+    v[1] = r.y;
+    v[2] = r.z;
+    v[3] = r.w;
+  }
+  __device__ __forceinline__ void zero() { v[0] = v[1] = v[2] = v[3] = 0u; }
+  static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c,
+                                           false);
+  }
+  __device__ __forceinline__ float dot(const uint4& k) const {
+    float a = dot2(k.x, v[0], 0.f);
+    a = dot2(k.y, v[1], a);
+    a = dot2(k.z, v[2], a);
+    a = dot2(k.w, v[3], a);
+    return a;
+  }
+};
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// Slot i of lane l carries head (i ^ c(l)), c(l) = bit_reverse(l & (GP-1)).  A stage with partner
+// l ^ M keeps the lower half of the slots and adds the partner's upper half, which carries the same
+// heads.  After log2(GP) stages slot 0 is the dot product of head c(l) summed over GP lanes.
+template <int N, int M>
+__device__ __forceinline__ float head_scatter(float (&v)[N]) {
+  if constexpr (N == 1) {
+    return v[0];
+  } else {
+    float w[N / 2];
+#pragma unroll
+    for (int i = 0; i < N / 2; ++i) w[i] = v[i] + lane_xor_f32<M>(v[i + N / 2]);
+    return head_scatter<N / 2, M * 2>(w);
+  }
+}
+
+// Sum over the remaining lane bits FROM .. LPR/2 of a token row (every lane gets the total).
+template <int FROM, int LPR>
+__device__ __forceinline__ float row_all_reduce(float v) {
+  if constexpr (FROM >= LPR) {
+    return v;
+  } else if constexpr (FROM == 4 && LPR >= 16) {
+    v += dpp_f32<0x124>(v);  // row_ror:4
+    v += dpp_f32<0x128>(v);  // row_ror:8 -> total over the four quads of the 16-lane row
+    return row_all_reduce<16, LPR>(v);
+  } else if constexpr (FROM == 8 && LPR >= 16) {
+    v += dpp_f32<0x128>(v);  // row_ror:8 is lane ^ 8 inside a 16-lane row
+    return row_all_reduce<16, LPR>(v);
+  } else {
+    v += lane_xor_f32<FROM>(v);
+    return row_all_reduce<FROM * 2, LPR>(v);
+  }
+}
+
+// acc[h][:] *= alpha of head h, which lives on lane position bit_reverse(h) of each GP-lane group.
+template <int G, int GP, int EPL, int H = 0>
+__device__ __forceinline__ void rescale_acc(float (&acc)[G][EPL], float alpha) {
+  if constexpr (H < G) {
+    const float a = group_bcast_f32<GP, bit_reverse<ilog2(GP)>(H)>(alpha);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[H][e] *= a;
+    rescale_acc<G, GP, EPL, H + 1>(acc, alpha);
+  }
+}
+
+// acc[h][:] += prob of head h (broadcast as above) * v[:].
+template <int G, int GP, int EPL, int H = 0>
+__device__ __forceinline__ void accumulate_pv(float (&acc)[G][EPL], float prob, const float (&v)[EPL]) {
+  if constexpr (H < G) {
+    const float ph = group_bcast_f32<GP, bit_reverse<ilog2(GP)>(H)>(prob);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[H][e] = fmaf(ph, v[e], acc[H][e]);
+    accumulate_pv<G, GP, EPL, H + 1>(acc, prob, v);
+  }
+}
+
+struct DecodeParams {
+  const void* q;
+  const void* k_pool;
+  const void* v_pool;
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  void* out;
+  float* partials;
+  float scale_log2e;
+  int num_kv_heads, num_q_heads, max_blocks, log2_block, splits, xcd_map, g_real;
+};
+
+template <typename T, int D, int G>
+struct Tile {
+  using Geo = RowGeom<T, D>;
+  static constexpr int EPL = Geo::kPerVec;
+  static constexpr int LPR = Geo::kLanesPerRow;
+  static constexpr int TPL = Geo::kTokensPerLoad;
+  static constexpr int NLT = kLoadsPerTile;
+  static constexpr int TT = NLT * TPL;  // tokens per tile
+  static constexpr int GP = next_pow2(G);
+  static_assert(GP <= LPR && GP <= 8, "query group too large");
+
+  // Issue the 2*NLT wave-loads of tile `tile`.  A load whose first token lies beyond the last page is
+  // redirected to the last page (its tokens are masked later), so every address is inside the pool.
+  static __device__ __forceinline__ void issue(uint4 (&kb)[NLT], uint4 (&vb)[NLT], int tile, const T* k_pool,
+                                               const T* v_pool, const int32_t* bt, int npages, int log2_block,
+                                               int lane) {
+    const int tok0 = tile * TT;
+#pragma unroll
+    for (int i = 0; i < NLT; ++i) {
+      const int t = tok0 + i * TPL;
+      int pi = t >> log2_block;
+      pi = pi < npages ? pi : npages - 1;
+      const int phys = __builtin_amdgcn_readfirstlane(bt[pi]);
+      const int slot0 = t & ((1 << log2_block) - 1);
+      const int64_t vec = (((int64_t)phys << log2_block) + slot0) * LPR + lane;
+      kb[i] = load_vec(k_pool, vec);
+      vb[i] = load_vec(v_pool, vec);
+    }
+  }
+
+  static __device__ __forceinline__ void compute(uint4 (&kb)[NLT], uint4 (&vb)[NLT], int tile, int len, int grp,
+                                                 float scale_log2e, const QSlice<T> (&qs)[GP], float& m_run,
+                                                 float& l_run, float (&acc)[G][EPL]) {
+    const int tok0 = tile * TT;
+    float x[NLT];
+#pragma unroll
+    for (int i = 0; i < NLT; ++i) {
+      float sd[GP];
+#pragma unroll
+      for (int j = 0; j < GP; ++j) sd[j] = qs[j].dot(kb[i]);
+      float r = head_scatter<GP, 1>(sd);
+      r = row_all_reduce<GP, LPR>(r);
+      x[i] = r * scale_log2e;
+    }
+    if (tok0 + TT > len) {  // the tile reaches past the row: mask logits, keep junk V out of the sum
+#pragma unroll
+      for (int i = 0; i < NLT; ++i) {
+        const bool ok = tok0 + i * TPL + grp < len;
+        x[i] = ok ? x[i] : kNegInf;
+        if (!ok) vb[i] = make_uint4(0u, 0u, 0u, 0u);
+      }
+    }
+    float m_new = m_run;
+#pragma unroll
+    for (int i = 0; i < NLT; ++i) m_new = fmaxf(m_new, x[i]);
+    const float m_safe = m_new == kNegInf ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+    float pr[NLT];
+    float psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NLT; ++i) {
+      pr[i] = __builtin_amdgcn_exp2f(x[i] - m_safe);
+      psum += pr[i];
+    }
+    l_run = fmaf(l_run, alpha, psum);
+    const bool changed = m_new != m_run;
+    m_run = m_new;
+    if (__builtin_amdgcn_ballot_w64(changed) != 0ull) rescale_acc<G, GP, EPL>(acc, alpha);
+#pragma unroll
+    for (int i = 0; i < NLT; ++i) {
+      float ve[EPL];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) ve[e] = vec_elem<T>(vb[i], e);
+      accumulate_pv<G, GP, EPL>(acc, pr[i], ve);
+    }
+  }
+};
+
+template <typename T, int D, int G>
+__global__ __launch_bounds__(kThreads) void paged_decode_kernel(const DecodeParams p) {
+  using TL = Tile<T, D, G>;
+  constexpr int EPL = TL::EPL, LPR = TL::LPR, TPL = TL::TPL, NLT = TL::NLT, TT = TL::TT, GP = TL::GP;
+  constexpr int GBITS = ilog2(GP);
+  constexpr int NCONTRIB = kWaves * TPL;
+
+  __shared__ float sm_m[NCONTRIB][GP];
+  __shared__ float sm_l[NCONTRIB][GP];
+  __shared__ __attribute__((aligned(16))) float sm_acc[NCONTRIB][D];
+
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+  const int u = lane % LPR;    // which 16-byte slice of the token row
+  const int grp = lane / LPR;  // which token row of a wave-load
+  const int c_lane = bit_reverse<GBITS>(lane & (GP - 1));
+
+  int row, split;
+  {
+    const int b = (int)blockIdx.x;
+    if (p.xcd_map) {  // workgroup b runs on XCD b % 8: keep all splits of a row on one XCD
+      const int xcd = b & 7, k = b >> 3;
+      row = (k / p.splits) * 8 + xcd;
+      split = k % p.splits;
+    } else {
+      row = b / p.splits;
+      split = b % p.splits;
+    }
+  }
+  const int s = row / p.num_kv_heads;
+  const int hk = row % p.num_kv_heads;
+  const int len = p.seq_lens[s];
+  const int npages = (len + (1 << p.log2_block) - 1) >> p.log2_block;
+  const int ntiles = (len + TT - 1) / TT;
+  const int t_begin = (int)(((int64_t)split * ntiles) / p.splits);
+  const int t_end = (int)(((int64_t)(split + 1) * ntiles) / p.splits);
+  const int32_t* bt = p.block_table + (int64_t)row * p.max_blocks;
+  const T* k_pool = static_cast<const T*>(p.k_pool);
+  const T* v_pool = static_cast<const T*>(p.v_pool);
+
+  // query slices: slot i holds head (i ^ c_lane) of this KV head's group
+  QSlice<T> qs[GP];
+#pragma unroll
+  for (int i = 0; i < GP; ++i) {
+    const int head = i ^ c_lane;
+    if (head < p.g_real) {
+      qs[i].load(static_cast<const T*>(p.q) + ((int64_t)s * p.num_q_heads + hk * p.g_real + head) * D + u * EPL);
+    } else {
+      qs[i].zero();
+    }
+  }
+
+  float m_run = kNegInf;  // running max of head c_lane over this lane's stream of tokens
+  float l_run = 0.f;
+  float acc[G][EPL];
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
+
+  {
+    uint4 kb0[NLT], vb0[NLT], kb1[NLT], vb1[NLT];
+    int tile = t_begin + wave;
+    if (tile < t_end) TL::issue(kb0, vb0, tile, k_pool, v_pool, bt, npages, p.log2_block, lane);
+    while (tile < t_end) {
+      if (tile + kWaves < t_end) TL::issue(kb1, vb1, tile + kWaves, k_pool, v_pool, bt, npages, p.log2_block, lane);
+      TL::compute(kb0, vb0, tile, len, grp, p.scale_log2e, qs, m_run, l_run, acc);
+      tile += kWaves;
+      if (tile >= t_end) break;
+      if (tile + kWaves < t_end) TL::issue(kb0, vb0, tile + kWaves, k_pool, v_pool, bt, npages, p.log2_block, lane);
+      TL::compute(kb1, vb1, tile, len, grp, p.scale_log2e, qs, m_run, l_run, acc);
+      tile += kWaves;
+    }
+  }
+
+  // ---- merge the kWaves x TPL token streams of this workgroup through LDS, one head at a time ----
+  const int contrib = wave * TPL + grp;
+  if (u < GP) {
+    sm_m[contrib][c_lane] = m_run;
+    sm_l[contrib][c_lane] = l_run;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    float mm = kNegInf;
+    for (int c = 0; c < NCONTRIB; ++c) mm = fmaxf(mm, sm_m[c][h]);
+    const float ms = mm == kNegInf ? 0.f : mm;
+    const float f = __builtin_amdgcn_exp2f(sm_m[contrib][h] - ms);
+    float4* dst = reinterpret_cast<float4*>(&sm_acc[contrib][u * EPL]);
+#pragma unroll
+    for (int e = 0; e < EPL; e += 4)
+      dst[e / 4] = make_float4(acc[h][e] * f, acc[h][e + 1] * f, acc[h][e + 2] * f, acc[h][e + 3] * f);
+    __syncthreads();
+    const int d = (int)threadIdx.x;
+    if (d < D && h < p.g_real) {
+      float ll = 0.f;
+      for (int c = 0; c < NCONTRIB; ++c) ll = fmaf(sm_l[c][h], __builtin_amdgcn_exp2f(sm_m[c][h] - ms), ll);
+      float o = 0.f;
+      for (int c = 0; c < NCONTRIB; ++c) o += sm_acc[c][d];
+      if (p.splits == 1) {
+        const float r = ll > 0.f ? o / ll : 0.f;
+        const int64_t off = ((int64_t)s * p.num_q_heads + hk * p.g_real + h) * D + d;
+        if constexpr (sizeof(T) == 4) {
+          static_cast<float*>(p.out)[off] = r;
+        } else {
+          static_cast<uint16_t*>(p.out)[off] = f32_to_bf16(r);
+        }
+      } else {
+        float* part = p.partials + (((int64_t)row * p.splits + split) * p.g_real + h) * (D + 2);
+        part[d] = o;
+        if (d == 0) {
+          part[D] = mm;
+          part[D + 1] = ll;
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// Merge the split partials of one (sequence, query head): one workgroup of D threads.
+template <typename T, int D>
+__global__ __launch_bounds__(D) void paged_decode_reduce_kernel(const float* __restrict__ partials,
+                                                                void* __restrict__ out, int num_kv_heads, int g_real,
+                                                                int splits) {
+  const int sh = (int)blockIdx.x;  // s * Hq + hq
+  const int num_q_heads = num_kv_heads * g_real;
+  const int s = sh / num_q_heads, hq = sh % num_q_heads;
+  const int row = s * num_kv_heads + hq / g_real;
+  const int h = hq % g_real;
+  const int d = (int)threadIdx.x;
+  const float* base = partials + (((int64_t)row * splits) * g_real + h) * (D + 2);
+  const int64_t stride = (int64_t)g_real * (D + 2);
+  float mm = kNegInf;
+  for (int sp = 0; sp < splits; ++sp) mm = fmaxf(mm, base[sp * stride + D]);
+  const float ms = mm == kNegInf ? 0.f : mm;
+  float o = 0.f, l = 0.f;
+  for (int sp = 0; sp < splits; ++sp) {
+    const float w = __builtin_amdgcn_exp2f(base[sp * stride + D] - ms);
+    l = fmaf(base[sp * stride + D + 1], w, l);
+    o = fmaf(base[sp * stride + d], w, o);
+  }
+  const float r = l > 0.f ? o / l : 0.f;
+  const int64_t off = (int64_t)sh * D + d;
+  if constexpr (sizeof(T) == 4) {
+    static_cast<float*>(out)[off] = r;
+  } else {
+    static_cast<uint16_t*>(out)[off] = f32_to_bf16(r);
+  }
+}
+
+template <typename T, int D, int G>
+hipError_t launch_one(const DecodeArgs& a, hipStream_t stream) {
+  DecodeParams p;
+  p.q = a.q;
+  p.k_pool = a.k_pool;
+  p.v_pool = a.v_pool;
+  p.block_table = a.block_table;
+  p.seq_lens = a.seq_lens;
+  p.out = a.out;
+  p.partials = a.partials;
+  p.scale_log2e = a.scale * 1.4426950408889634f;
+  p.num_kv_heads = a.num_kv_heads;
+  p.num_q_heads = a.num_q_heads;
+  p.max_blocks = a.max_blocks;
+  p.log2_block = ilog2(a.block_size);
+  p.splits = a.splits;
+  p.g_real = a.num_q_heads / a.num_kv_heads;
+  const int64_t rows = (int64_t)a.num_seqs * a.num_kv_heads;
+  p.xcd_map = (a.xcd_map && rows % 8 == 0) ? 1 : 0;
+  const int64_t grid = rows * a.splits;
+  if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((paged_decode_kernel<T, D, G>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || a.splits == 1) return e;
+  hipLaunchKernelGGL((paged_decode_reduce_kernel<T, D>), dim3((unsigned)(a.num_seqs * a.num_q_heads)), dim3(D), 0,
+                     stream, a.partials, a.out, a.num_kv_heads, p.g_real, a.splits);
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t launch_group(const DecodeArgs& a, hipStream_t stream) {
+  const int g = a.num_q_heads / a.num_kv_heads;
+  switch (g) {
+    case 1: return launch_one<T, D, 1>(a, stream);
+    case 2: return launch_one<T, D, 2>(a, stream);
+    case 3: return launch_one<T, D, 3>(a, stream);
+    case 4: return launch_one<T, D, 4>(a, stream);
+    case 5: case 6: case 7: case 8: return launch_one<T, D, 8>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+size_t decode_partials_bytes(int num_seqs, int num_q_heads, int head_dim, int splits) {
+  if (splits <= 1) return 0;
+  return (size_t)num_seqs * num_q_heads * splits * (head_dim + 2) * sizeof(float);
+}
+
+hipError_t launch_paged_decode(const DecodeArgs& a, hipStream_t stream) {
+  if (a.is_bf16) {
+    if (a.head_dim == 64) return launch_group<bf16_t, 64>(a, stream);
+    if (a.head_dim == 128) return launch_group<bf16_t, 128>(a, stream);
+  } else {
+    if (a.head_dim == 64) return launch_group<float, 64>(a, stream);
+    if (a.head_dim == 128) return launch_group<float, 128>(a, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace pe

@@ -1,0 +1,238 @@
+// C-ABI layer of libpe (see include/pe.h): argument validation on the host, then kernel launches on
+// the caller's stream.  Nothing here allocates, frees or synchronises.
+#include "../../include/pe.h"
+
+#include "pe_launch.h"
+
+namespace {
+
+int g_options[PE_OPT_COUNT_] = {0 /* decode splits: auto */, 1 /* XCD-aware workgroup order */};
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// PE_OK if the descriptor names a shape the kernels are built for.
+int check_desc(const pe_cache_desc* d) {
+  if (d == nullptr) return PE_ERR_INVALID_ARG;
+  if (d->dtype != PE_F32 && d->dtype != PE_BF16) return PE_ERR_UNSUPPORTED;
+  if (d->num_seqs < 1 || d->num_kv_heads < 1 || d->num_q_heads < 1 || d->max_blocks < 1 || d->num_phys_blocks < 1)
+    return PE_ERR_INVALID_ARG;
+  if (d->num_q_heads % d->num_kv_heads != 0) return PE_ERR_INVALID_ARG;
+  if (d->num_q_heads / d->num_kv_heads > 8) return PE_ERR_UNSUPPORTED;
+  if (d->head_dim != 64 && d->head_dim != 128) return PE_ERR_UNSUPPORTED;
+  if (d->block_size != 16 && d->block_size != 32) return PE_ERR_UNSUPPORTED;
+  if (d->num_phys_blocks > 0x7fffffffLL) return PE_ERR_UNSUPPORTED;
+  if ((int64_t)d->num_seqs * d->num_kv_heads > 0x7fffffffLL / 64) return PE_ERR_UNSUPPORTED;
+  return PE_OK;
+}
+
+// Number of splits of a row in pe_paged_decode: enough workgroups to give each of the 256 CUs
+// about four, but no split shorter than a handful of tiles.
+int decode_splits(const pe_cache_desc* d) {
+  if (g_options[PE_OPT_DECODE_SPLITS] > 0) return g_options[PE_OPT_DECODE_SPLITS];
+  const int64_t rows = (int64_t)d->num_seqs * d->num_kv_heads;
+  const int64_t target_groups = 1024;
+  int64_t splits = (target_groups + rows - 1) / rows;
+  const int64_t max_tokens = (int64_t)d->max_blocks * d->block_size;
+  const int64_t max_by_len = max_tokens / 128 > 1 ? max_tokens / 128 : 1;
+  if (splits > max_by_len) splits = max_by_len;
+  if (splits > 64) splits = 64;
+  if (splits < 1) splits = 1;
+  return (int)splits;
+}
+
+int check_workspace(const void* ws, size_t have, size_t need) {
+  if (need == 0) return PE_OK;
+  if (ws == nullptr || have < need || !aligned(ws, 256)) return PE_ERR_WORKSPACE;
+  return PE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pe_version(void) { return 100; }
+
+const char* pe_status_string(int status) {
+  switch (status) {
+    case PE_OK: return "ok";
+    case PE_ERR_INVALID_ARG: return "invalid argument";
+    case PE_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    case PE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case PE_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int pe_set_option(int key, int value) {
+  if (key < 0 || key >= PE_OPT_COUNT_) return PE_ERR_INVALID_ARG;
+  if (key == PE_OPT_DECODE_SPLITS && (value < 0 || value > 256)) return PE_ERR_INVALID_ARG;
+  if (key == PE_OPT_DECODE_XCD_MAP && value != 0 && value != 1) return PE_ERR_INVALID_ARG;
+  g_options[key] = value;
+  return PE_OK;
+}
+
+int pe_get_option(int key) {
+  if (key < 0 || key >= PE_OPT_COUNT_) return PE_ERR_INVALID_ARG;
+  return g_options[key];
+}
+
+size_t pe_workspace_bytes(int op, const pe_cache_desc* desc, int64_t total_tokens) {
+  if (check_desc(desc) != PE_OK) return 0;
+  switch (op) {
+    case PE_OP_PAGED_DECODE:
+      return pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, decode_splits(desc));
+    case PE_OP_PREFILL_PRUNE:
+      if (total_tokens < 0) return 0;
+      return pe::prune_workspace_bytes(desc->num_seqs, desc->num_kv_heads, total_tokens);
+    default:
+      return 0;
+  }
+}
+
+int pe_score_blocks(const pe_cache_desc* desc, const void* k_pool, const void* v_pool, const int32_t* block_table,
+                    const int32_t* seq_lens, float* scores_out, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  const int st = check_desc(desc);
+  if (st != PE_OK) return st;
+  if (!k_pool || !v_pool || !block_table || !seq_lens || !scores_out) return PE_ERR_INVALID_ARG;
+  if (!aligned(k_pool, 16) || !aligned(v_pool, 16)) return PE_ERR_INVALID_ARG;
+  pe::ScoreArgs a;
+  a.k_pool = k_pool;
+  a.v_pool = v_pool;
+  a.block_table = block_table;
+  a.seq_lens = seq_lens;
+  a.scores = scores_out;
+  a.num_seqs = desc->num_seqs;
+  a.num_kv_heads = desc->num_kv_heads;
+  a.head_dim = desc->head_dim;
+  a.block_size = desc->block_size;
+  a.max_blocks = desc->max_blocks;
+  a.is_bf16 = desc->dtype == PE_BF16;
+  return pe::launch_score_blocks(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
+}
+
+int pe_prefill_prune(const pe_cache_desc* desc, const void* k_in, const void* v_in, const int32_t* cu_seqlens,
+                     int64_t total_tokens, int32_t max_seqlen, int32_t budget_tokens, void* k_pool, void* v_pool,
+                     const int32_t* block_table, int32_t* seq_lens_out, int32_t* kept_idx_out, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+  const int st = check_desc(desc);
+  if (st != PE_OK) return st;
+  if (!cu_seqlens || !k_pool || !v_pool || !block_table || !seq_lens_out) return PE_ERR_INVALID_ARG;
+  if (total_tokens < 0 || total_tokens > 0x7fffffffLL || max_seqlen < 0 || max_seqlen > total_tokens)
+    return PE_ERR_INVALID_ARG;
+  if (total_tokens > 0 && (!k_in || !v_in)) return PE_ERR_INVALID_ARG;
+  if (budget_tokens <= 0 || budget_tokens % desc->block_size != 0) return PE_ERR_INVALID_ARG;
+  if (!aligned(k_pool, 16) || !aligned(v_pool, 16) || !aligned(k_in, 16) || !aligned(v_in, 16))
+    return PE_ERR_INVALID_ARG;
+  const int ws = check_workspace(workspace, workspace_bytes,
+                                 pe::prune_workspace_bytes(desc->num_seqs, desc->num_kv_heads, total_tokens));
+  if (ws != PE_OK) return ws;
+  pe::PruneArgs a;
+  a.k_in = k_in;
+  a.v_in = v_in;
+  a.cu_seqlens = cu_seqlens;
+  a.k_pool = k_pool;
+  a.v_pool = v_pool;
+  a.block_table = block_table;
+  a.seq_lens_out = seq_lens_out;
+  a.kept_idx_out = kept_idx_out;
+  a.workspace = workspace;
+  a.total_tokens = total_tokens;
+  a.max_seqlen = max_seqlen;
+  a.budget = budget_tokens;
+  a.num_seqs = desc->num_seqs;
+  a.num_kv_heads = desc->num_kv_heads;
+  a.head_dim = desc->head_dim;
+  a.block_size = desc->block_size;
+  a.max_blocks = desc->max_blocks;
+  a.is_bf16 = desc->dtype == PE_BF16;
+  return pe::launch_prefill_prune(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
+}
+
+int pe_evict_blocks(const pe_cache_desc* desc, const float* scores, int32_t* block_table, int32_t* seq_lens,
+                    int32_t budget_tokens, int32_t* evicted_logical_out, int32_t* freed_phys_out, void* stream) {
+  const int st = check_desc(desc);
+  if (st != PE_OK) return st;
+  if (!scores || !block_table || !seq_lens || !evicted_logical_out || !freed_phys_out) return PE_ERR_INVALID_ARG;
+  if (budget_tokens <= 0 || budget_tokens % desc->block_size != 0) return PE_ERR_INVALID_ARG;
+  pe::EvictArgs a;
+  a.scores = scores;
+  a.block_table = block_table;
+  a.seq_lens = seq_lens;
+  a.evicted_logical = evicted_logical_out;
+  a.freed_phys = freed_phys_out;
+  a.num_seqs = desc->num_seqs;
+  a.num_kv_heads = desc->num_kv_heads;
+  a.block_size = desc->block_size;
+  a.max_blocks = desc->max_blocks;
+  a.budget = budget_tokens;
+  return pe::launch_evict_blocks(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
+}
+
+int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool, const void* v_pool,
+                    const int32_t* block_table, const int32_t* seq_lens, float softmax_scale, void* out,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  const int st = check_desc(desc);
+  if (st != PE_OK) return st;
+  if (!q || !k_pool || !v_pool || !block_table || !seq_lens || !out) return PE_ERR_INVALID_ARG;
+  if (!aligned(k_pool, 16) || !aligned(v_pool, 16) || !aligned(q, 16)) return PE_ERR_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale) || softmax_scale - softmax_scale != 0.f) return PE_ERR_INVALID_ARG;
+  const int splits = decode_splits(desc);
+  const int ws = check_workspace(
+      workspace, workspace_bytes,
+      pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, splits));
+  if (ws != PE_OK) return ws;
+  pe::DecodeArgs a;
+  a.q = q;
+  a.k_pool = k_pool;
+  a.v_pool = v_pool;
+  a.block_table = block_table;
+  a.seq_lens = seq_lens;
+  a.out = out;
+  a.partials = static_cast<float*>(workspace);
+  a.scale = softmax_scale;
+  a.num_seqs = desc->num_seqs;
+  a.num_kv_heads = desc->num_kv_heads;
+  a.num_q_heads = desc->num_q_heads;
+  a.head_dim = desc->head_dim;
+  a.block_size = desc->block_size;
+  a.max_blocks = desc->max_blocks;
+  a.splits = splits;
+  a.xcd_map = g_options[PE_OPT_DECODE_XCD_MAP];
+  a.is_bf16 = desc->dtype == PE_BF16;
+  return pe::launch_paged_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
+}
+
+int pe_append_kv(const pe_cache_desc* desc, const void* new_k, const void* new_v, void* k_pool, void* v_pool,
+                 int32_t* block_table, int32_t* seq_lens, int32_t* freed_phys, const int32_t* spare,
+                 int32_t* spare_used, int32_t n_spare, void* stream) {
+  const int st = check_desc(desc);
+  if (st != PE_OK) return st;
+  if (!new_k || !new_v || !k_pool || !v_pool || !block_table || !seq_lens || !freed_phys || !spare || !spare_used)
+    return PE_ERR_INVALID_ARG;
+  if (n_spare < 1) return PE_ERR_INVALID_ARG;
+  if (!aligned(k_pool, 16) || !aligned(v_pool, 16) || !aligned(new_k, 16) || !aligned(new_v, 16))
+    return PE_ERR_INVALID_ARG;
+  pe::AppendArgs a;
+  a.new_k = new_k;
+  a.new_v = new_v;
+  a.k_pool = k_pool;
+  a.v_pool = v_pool;
+  a.block_table = block_table;
+  a.seq_lens = seq_lens;
+  a.freed_phys = freed_phys;
+  a.spare = spare;
+  a.spare_used = spare_used;
+  a.n_spare = n_spare;
+  a.num_seqs = desc->num_seqs;
+  a.num_kv_heads = desc->num_kv_heads;
+  a.head_dim = desc->head_dim;
+  a.block_size = desc->block_size;
+  a.max_blocks = desc->max_blocks;
+  a.is_bf16 = desc->dtype == PE_BF16;
+  return pe::launch_append_kv(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
+}
+
+}  // extern "C"

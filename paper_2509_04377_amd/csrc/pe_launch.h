@@ -1,0 +1,82 @@
+// Host-side launch interfaces between the C-ABI layer (pe_api.hip) and the kernel translation units.
+// Arguments are already validated by the caller: shapes are supported, pointers are non-null.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace pe {
+
+struct ScoreArgs {
+  const void* k_pool;
+  const void* v_pool;
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  float* scores;
+  int num_seqs, num_kv_heads, head_dim, block_size, max_blocks;
+  bool is_bf16;
+};
+hipError_t launch_score_blocks(const ScoreArgs& a, hipStream_t stream);
+
+struct EvictArgs {
+  const float* scores;
+  int32_t* block_table;
+  int32_t* seq_lens;
+  int32_t* evicted_logical;
+  int32_t* freed_phys;
+  int num_seqs, num_kv_heads, block_size, max_blocks, budget;
+};
+hipError_t launch_evict_blocks(const EvictArgs& a, hipStream_t stream);
+
+struct AppendArgs {
+  const void* new_k;
+  const void* new_v;
+  void* k_pool;
+  void* v_pool;
+  int32_t* block_table;
+  int32_t* seq_lens;
+  int32_t* freed_phys;
+  const int32_t* spare;
+  int32_t* spare_used;
+  int n_spare, num_seqs, num_kv_heads, head_dim, block_size, max_blocks;
+  bool is_bf16;
+};
+hipError_t launch_append_kv(const AppendArgs& a, hipStream_t stream);
+
+struct DecodeArgs {
+  const void* q;
+  const void* k_pool;
+  const void* v_pool;
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  void* out;
+  float* partials;  // workspace: [rows][splits][G][D + 2] fp32 (unused when splits == 1)
+  float scale;
+  int num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, max_blocks;
+  int splits;
+  int xcd_map;
+  bool is_bf16;
+};
+hipError_t launch_paged_decode(const DecodeArgs& a, hipStream_t stream);
+size_t decode_partials_bytes(int num_seqs, int num_q_heads, int head_dim, int splits);
+
+struct PruneArgs {
+  const void* k_in;
+  const void* v_in;
+  const int32_t* cu_seqlens;
+  void* k_pool;
+  void* v_pool;
+  const int32_t* block_table;
+  int32_t* seq_lens_out;
+  int32_t* kept_idx_out;  // may be null
+  void* workspace;
+  int64_t total_tokens;
+  int max_seqlen, budget;
+  int num_seqs, num_kv_heads, head_dim, block_size, max_blocks;
+  bool is_bf16;
+};
+hipError_t launch_prefill_prune(const PruneArgs& a, hipStream_t stream);
+size_t prune_workspace_bytes(int num_seqs, int num_kv_heads, int64_t total_tokens);
+
+}  // namespace pe

@@ -1,0 +1,405 @@
+// Prefill token pruning (Alg. 2, the steps after the prompt's attention): score every prompt token,
+// evict the E = max(0, L - C) tokens that come first under (score ascending, index ascending), and
+// write the survivors, order kept, into the row's pages.
+//
+// Four kernels on one stream:
+//   1. token_scores:  sweep of the packed K/V prompt; S_i = ||V_i||/||K_i|| in fp64, rounded once to
+//                     fp32, stored per KV head as a contiguous run  scores[hk][token].
+//   2. select:        per row, radix select (4 passes of 8 bits, most significant first) on the fp32 bit
+//                     patterns (scores are >= +0, so they order like unsigned integers) for the E-th
+//                     smallest score T and the number q of tokens equal to T that must go.
+//   3. chunk_counts:  per row and chunk of 1024 tokens, how many scores are > T and how many == T.
+//   4. gather:        per row and chunk, an index-ordered scan turns those counts into the destination
+//                     of every kept token; token rows are then copied with 16-byte lane accesses.
+// A token is kept iff score > T, or score == T and at least q equal-score tokens precede it.
+#include "pe_device.h"
+#include "pe_launch.h"
+#include "pe_norms.h"
+
+namespace pe {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kChunk = 1024;  // tokens per chunk in kernels 3 and 4 (4 per thread)
+constexpr int kTokPerThread = kChunk / kThreads;
+
+__host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Workspace {
+  float* scores;  // [Hk][total_tokens]
+  uint32_t* sel;  // [rows][2]: threshold bits T, tie quota q
+  int32_t* cnt;   // [Hk][chunk_slots][2]: (#score > T, #score == T) per chunk
+  int64_t chunk_slots;
+};
+
+__host__ inline int64_t chunk_slots_for(int64_t total_tokens, int num_seqs) {
+  return total_tokens / kChunk + num_seqs + 1;
+}
+
+__host__ inline Workspace carve(void* base, int num_seqs, int num_kv_heads, int64_t total_tokens) {
+  Workspace w;
+  char* p = static_cast<char*>(base);
+  w.scores = reinterpret_cast<float*>(p);
+  p += align256(sizeof(float) * (size_t)num_kv_heads * (size_t)total_tokens);
+  w.sel = reinterpret_cast<uint32_t*>(p);
+  p += align256(sizeof(uint32_t) * 2 * (size_t)num_seqs * num_kv_heads);
+  w.cnt = reinterpret_cast<int32_t*>(p);
+  w.chunk_slots = chunk_slots_for(total_tokens, num_seqs);
+  return w;
+}
+
+// Chunk slot of (sequence s, local chunk c): sequences never overlap because
+// floor((a+b)/n) + 1 >= floor(a/n) + ceil(b/n).
+__device__ __forceinline__ int64_t chunk_slot(int cu_s, int s, int c) { return (int64_t)(cu_s / kChunk) + s + c; }
+
+// ---- 1. token scores -------------------------------------------------------------------------------
+// The packed prompt is a flat array of (token, head) rows of D elements.  A wave-load covers TPL rows;
+// a wave handles kIters groups of NL wave-loads for K and for V, software-pipelined.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void token_scores_kernel(const T* __restrict__ k_in,
+                                                                const T* __restrict__ v_in,
+                                                                float* __restrict__ scores, int64_t total_rows,
+                                                                int64_t total_tokens, int num_kv_heads) {
+  using G = RowGeom<T, D>;
+  constexpr int LPR = G::kLanesPerRow;
+  constexpr int TPL = G::kTokensPerLoad;
+  constexpr int NL = 4;
+  constexpr int kRowsPerStep = NL * TPL;
+  constexpr int kIters = 4;
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+  const int grp = lane / LPR;
+  const int64_t row0 = ((int64_t)blockIdx.x * kWaves + wave) * (kIters * kRowsPerStep);
+
+  uint4 kb[2][NL], vb[2][NL];
+  auto issue = [&](int buf, int64_t base_row) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      const int64_t r = base_row + i * TPL + grp;
+      if (r < total_rows) {
+        const int64_t vec = (base_row + i * TPL) * LPR + lane;
+        kb[buf][i] = load_vec(k_in, vec);
+        vb[buf][i] = load_vec(v_in, vec);
+      } else {
+        kb[buf][i] = make_uint4(0u, 0u, 0u, 0u);
+        vb[buf][i] = make_uint4(0u, 0u, 0u, 0u);
+      }
+    }
+  };
+  issue(0, row0);
+#pragma unroll
+  for (int it = 0; it < kIters; ++it) {
+    const int64_t base_row = row0 + (int64_t)it * kRowsPerStep;
+    if (it + 1 < kIters) issue((it + 1) & 1, base_row + kRowsPerStep);
+    if (base_row >= total_rows) break;
+    const int buf = it & 1;
+    double part[2 * NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      part[i] = sumsq_vec<T>(kb[buf][i], 0.0);
+      part[NL + i] = sumsq_vec<T>(vb[buf][i], 0.0);
+    }
+    const double ratio = token_ratio_from_partials<NL, LPR>(part, lane);
+    // the lane at position 2*k of its row group (k < NL) stores the row of wave-load bit_reverse(k)
+    const int uu = lane % LPR;
+    if ((uu & 1) == 0 && uu < 2 * NL) {
+      const int i = bit_reverse<ilog2(NL)>(uu >> 1);
+      const int64_t r = base_row + i * TPL + grp;
+      if (r < total_rows) {
+        const int64_t tok = r / num_kv_heads;
+        const int h = (int)(r % num_kv_heads);
+        scores[(int64_t)h * total_tokens + tok] = (float)ratio;
+      }
+    }
+  }
+}
+
+// ---- 2. per-row radix select ------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void select_kernel(const float* __restrict__ scores,
+                                                          const int32_t* __restrict__ cu_seqlens,
+                                                          uint32_t* __restrict__ sel, int32_t* __restrict__ seq_lens_out,
+                                                          int32_t* __restrict__ kept_idx_out, int64_t total_tokens,
+                                                          int num_kv_heads, int budget) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t sh_prefix, sh_k;
+  const int row = (int)blockIdx.x;
+  const int s = row / num_kv_heads, h = row % num_kv_heads;
+  const int t0 = cu_seqlens[s];
+  const int L = cu_seqlens[s + 1] - t0;
+  const int keep = L < budget ? L : budget;
+  const int E = L - keep;
+  const uint32_t* bits = reinterpret_cast<const uint32_t*>(scores) + (int64_t)h * total_tokens + t0;
+  const int tid = (int)threadIdx.x;
+
+  if (h == 0 && tid == 0) seq_lens_out[s] = keep;
+  if (kept_idx_out != nullptr)
+    for (int i = keep + tid; i < budget; i += kThreads) kept_idx_out[(int64_t)row * budget + i] = -1;
+
+  if (E == 0) {  // nothing to evict: T = +0.0, q = 0 keeps every token (scores are >= +0)
+    if (tid == 0) {
+      sel[2 * row] = 0u;
+      sel[2 * row + 1] = 0u;
+    }
+    return;
+  }
+  uint32_t prefix = 0u, mask = 0u;
+  uint32_t k = (uint32_t)(E - 1);  // 0-based rank of the threshold element among the remaining ones
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    hist[tid] = 0u;
+    __syncthreads();
+    for (int i = tid; i < L; i += kThreads) {
+      const uint32_t b = bits[i];
+      if ((b & mask) == prefix) atomicAdd(&hist[(b >> shift) & 0xffu], 1u);
+    }
+    __syncthreads();
+    if (tid < kWave) {  // one wave: find the digit whose cumulative count passes k
+      uint32_t c[4], tot = 0u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        c[j] = hist[tid * 4 + j];
+        tot += c[j];
+      }
+      uint32_t incl = tot;  // inclusive scan over the 64 lanes
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_up((int)incl, off, kWave);
+        if (tid >= off) incl += o;
+      }
+      uint32_t before = incl - tot;
+      if (k >= before && k < incl) {  // exactly one lane
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (k >= before && k < before + c[j]) {
+            sh_prefix = prefix | ((uint32_t)(tid * 4 + j) << shift);
+            sh_k = k - before;
+          }
+          before += c[j];
+        }
+      }
+    }
+    __syncthreads();
+    prefix = sh_prefix;
+    k = sh_k;
+    mask |= 0xffu << shift;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    sel[2 * row] = prefix;     // T
+    sel[2 * row + 1] = k + 1;  // q: the first q tokens (index order) with score == T are evicted
+  }
+}
+
+// ---- 3. per-chunk counts ------------------------------------------------------------------------------
+__device__ __forceinline__ int block_sum(int v, int* sh /* [kWaves] */) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+  const int wave = (int)(threadIdx.x / kWave);
+  __syncthreads();
+  if (lane_id() == 0) sh[wave] = v;
+  __syncthreads();
+  int t = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) t += sh[w];
+  return t;
+}
+
+__global__ __launch_bounds__(kThreads) void chunk_counts_kernel(const float* __restrict__ scores,
+                                                                const int32_t* __restrict__ cu_seqlens,
+                                                                const uint32_t* __restrict__ sel,
+                                                                int32_t* __restrict__ cnt, int64_t total_tokens,
+                                                                int64_t chunk_slots, int num_kv_heads,
+                                                                int chunks_per_row) {
+  __shared__ int sh[kWaves];
+  const int row = (int)(blockIdx.x / chunks_per_row);
+  const int chunk = (int)(blockIdx.x % chunks_per_row);
+  const int s = row / num_kv_heads, h = row % num_kv_heads;
+  const int t0 = cu_seqlens[s];
+  const int L = cu_seqlens[s + 1] - t0;
+  if (chunk * kChunk >= L) return;
+  const uint32_t T = sel[2 * row];
+  const uint32_t* bits = reinterpret_cast<const uint32_t*>(scores) + (int64_t)h * total_tokens + t0;
+  int gt = 0, eq = 0;
+#pragma unroll
+  for (int j = 0; j < kTokPerThread; ++j) {
+    const int i = chunk * kChunk + (int)threadIdx.x * kTokPerThread + j;
+    if (i < L) {
+      const uint32_t b = bits[i];
+      gt += b > T;
+      eq += b == T;
+    }
+  }
+  gt = block_sum(gt, sh);
+  eq = block_sum(eq, sh);
+  if (threadIdx.x == 0) {
+    int32_t* c = cnt + ((int64_t)h * chunk_slots + chunk_slot(t0, s, chunk)) * 2;
+    c[0] = gt;
+    c[1] = eq;
+  }
+}
+
+// ---- 4. gather ----------------------------------------------------------------------------------------
+template <int VEC_PER_ROW>
+__global__ __launch_bounds__(kThreads) void gather_kernel(const uint4* __restrict__ k_in, const uint4* __restrict__ v_in,
+                                                          const float* __restrict__ scores,
+                                                          const int32_t* __restrict__ cu_seqlens,
+                                                          const uint32_t* __restrict__ sel,
+                                                          const int32_t* __restrict__ cnt,
+                                                          const int32_t* __restrict__ block_table,
+                                                          uint4* __restrict__ k_pool, uint4* __restrict__ v_pool,
+                                                          int32_t* __restrict__ kept_idx_out, int64_t total_tokens,
+                                                          int64_t chunk_slots, int num_kv_heads, int chunks_per_row,
+                                                          int block_size, int max_blocks, int budget) {
+  __shared__ int sh[kWaves];
+  __shared__ int wave_off[kWaves][2];
+  __shared__ int32_t src_tok[kChunk];  // kept tokens of this chunk: in-sequence index
+  __shared__ int32_t dst_pos[kChunk];  // and their position in the pruned row
+  __shared__ int n_kept_sh;
+  const int row = (int)(blockIdx.x / chunks_per_row);
+  const int chunk = (int)(blockIdx.x % chunks_per_row);
+  const int s = row / num_kv_heads, h = row % num_kv_heads;
+  const int t0 = cu_seqlens[s];
+  const int L = cu_seqlens[s + 1] - t0;
+  if (chunk * kChunk >= L) return;
+  const int tid = (int)threadIdx.x;
+  const int lane = lane_id();
+  const int wave = tid / kWave;
+  const uint32_t T = sel[2 * row];
+  const int q = (int)sel[2 * row + 1];
+
+  // counts of all earlier chunks of this row
+  int gt_before = 0, eq_before = 0;
+  {
+    const int32_t* c = cnt + ((int64_t)h * chunk_slots + chunk_slot(t0, s, 0)) * 2;
+    for (int cc = tid; cc < chunk; cc += kThreads) {
+      gt_before += c[2 * cc];
+      eq_before += c[2 * cc + 1];
+    }
+    gt_before = block_sum(gt_before, sh);
+    eq_before = block_sum(eq_before, sh);
+  }
+
+  // this thread's kTokPerThread consecutive tokens
+  const uint32_t* bits = reinterpret_cast<const uint32_t*>(scores) + (int64_t)h * total_tokens + t0;
+  const int i0 = chunk * kChunk + tid * kTokPerThread;
+  uint32_t b[kTokPerThread];
+  int n_gt = 0, n_eq = 0;
+#pragma unroll
+  for (int j = 0; j < kTokPerThread; ++j) {
+    b[j] = (i0 + j < L) ? bits[i0 + j] : 0u;
+    const bool in = i0 + j < L;
+    n_gt += in && b[j] > T;
+    n_eq += in && b[j] == T;
+  }
+  // exclusive scan of (n_gt, n_eq) over the 256 threads, in thread (= index) order
+  int inc_gt = n_gt, inc_eq = n_eq;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int a = __shfl_up(inc_gt, off, kWave);
+    const int c2 = __shfl_up(inc_eq, off, kWave);
+    if (lane >= off) {
+      inc_gt += a;
+      inc_eq += c2;
+    }
+  }
+  if (lane == kWave - 1) {
+    wave_off[wave][0] = inc_gt;
+    wave_off[wave][1] = inc_eq;
+  }
+  __syncthreads();
+  int ex_gt = inc_gt - n_gt + gt_before, ex_eq = inc_eq - n_eq + eq_before;
+  for (int w = 0; w < wave; ++w) {
+    ex_gt += wave_off[w][0];
+    ex_eq += wave_off[w][1];
+  }
+  // kept tokens before this chunk's start (needed to make dst relative positions dense in LDS)
+  const int kept_before_chunk = gt_before + (eq_before > q ? eq_before - q : 0);
+#pragma unroll
+  for (int j = 0; j < kTokPerThread; ++j) {
+    const bool in = i0 + j < L;
+    const bool is_gt = in && b[j] > T;
+    const bool is_eq = in && b[j] == T;
+    const bool kept = is_gt || (is_eq && ex_eq >= q);
+    if (kept) {
+      const int pos = ex_gt + (ex_eq > q ? ex_eq - q : 0);  // kept tokens before this one in the row
+      const int slot = pos - kept_before_chunk;
+      src_tok[slot] = i0 + j;
+      dst_pos[slot] = pos;
+    }
+    ex_gt += is_gt;
+    ex_eq += is_eq;
+  }
+  if (tid == kThreads - 1) n_kept_sh = ex_gt + (ex_eq > q ? ex_eq - q : 0) - kept_before_chunk;
+  __syncthreads();
+  const int n_kept = n_kept_sh;
+
+  // copy the kept rows: VEC_PER_ROW lanes per token row, K and V
+  const int32_t* bt = block_table + (int64_t)row * max_blocks;
+  constexpr int kRowsPerPass = kThreads / VEC_PER_ROW;
+  const int u = tid % VEC_PER_ROW, r = tid / VEC_PER_ROW;
+  for (int base = 0; base < n_kept; base += kRowsPerPass) {
+    const int e = base + r;
+    if (e < n_kept) {
+      const int tok = src_tok[e], pos = dst_pos[e];
+      const int64_t src = ((int64_t)(t0 + tok) * num_kv_heads + h) * VEC_PER_ROW + u;
+      const int64_t dst = ((int64_t)bt[pos / block_size] * block_size + pos % block_size) * VEC_PER_ROW + u;
+      k_pool[dst] = k_in[src];
+      v_pool[dst] = v_in[src];
+      if (kept_idx_out != nullptr && u == 0) kept_idx_out[(int64_t)row * budget + pos] = tok;
+    }
+  }
+}
+
+template <typename T, int D>
+hipError_t launch(const PruneArgs& a, hipStream_t stream) {
+  using G = RowGeom<T, D>;
+  const Workspace w = carve(a.workspace, a.num_seqs, a.num_kv_heads, a.total_tokens);
+  const int rows = a.num_seqs * a.num_kv_heads;
+  const int64_t total_rows = a.total_tokens * a.num_kv_heads;
+  hipError_t e;
+  if (total_rows > 0) {
+    const int64_t rows_per_group = (int64_t)kWaves * 4 * 4 * G::kTokensPerLoad;
+    const int64_t grid = (total_rows + rows_per_group - 1) / rows_per_group;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((token_scores_kernel<T, D>), dim3((unsigned)grid), dim3(kThreads), 0, stream,
+                       (const T*)a.k_in, (const T*)a.v_in, w.scores, total_rows, a.total_tokens, a.num_kv_heads);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(select_kernel, dim3((unsigned)rows), dim3(kThreads), 0, stream, w.scores, a.cu_seqlens, w.sel,
+                     a.seq_lens_out, a.kept_idx_out, a.total_tokens, a.num_kv_heads, a.budget);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const int chunks_per_row = (a.max_seqlen + kChunk - 1) / kChunk;
+  if (chunks_per_row == 0) return hipSuccess;
+  const int64_t grid2 = (int64_t)rows * chunks_per_row;
+  if (grid2 > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(chunk_counts_kernel, dim3((unsigned)grid2), dim3(kThreads), 0, stream, w.scores, a.cu_seqlens,
+                     w.sel, w.cnt, a.total_tokens, w.chunk_slots, a.num_kv_heads, chunks_per_row);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  constexpr int VPR = G::kLanesPerRow;
+  hipLaunchKernelGGL((gather_kernel<VPR>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, (const uint4*)a.k_in,
+                     (const uint4*)a.v_in, w.scores, a.cu_seqlens, w.sel, w.cnt, a.block_table, (uint4*)a.k_pool,
+                     (uint4*)a.v_pool, a.kept_idx_out, a.total_tokens, w.chunk_slots, a.num_kv_heads, chunks_per_row,
+                     a.block_size, a.max_blocks, a.budget);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t prune_workspace_bytes(int num_seqs, int num_kv_heads, int64_t total_tokens) {
+  return align256(sizeof(float) * (size_t)num_kv_heads * (size_t)total_tokens) +
+         align256(sizeof(uint32_t) * 2 * (size_t)num_seqs * num_kv_heads) +
+         align256(sizeof(int32_t) * 2 * (size_t)num_kv_heads * (size_t)chunk_slots_for(total_tokens, num_seqs));
+}
+
+hipError_t launch_prefill_prune(const PruneArgs& a, hipStream_t stream) {
+  if (a.is_bf16) {
+    if (a.head_dim == 64) return launch<bf16_t, 64>(a, stream);
+    if (a.head_dim == 128) return launch<bf16_t, 128>(a, stream);
+  } else {
+    if (a.head_dim == 64) return launch<float, 64>(a, stream);
+    if (a.head_dim == 128) return launch<float, 128>(a, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace pe

@@ -1,0 +1,65 @@
+"""Multi-layer decode driver over one shared page pool (host-side sequencing of C-ABI calls only).
+
+All layers' pages live in one physical pool; the block table is [layers * S, Hk, max_blocks] with
+layer l owning rows l*S .. (l+1)*S - 1 ("layers folded into the sequence dimension").  Scoring,
+eviction and the prefill prune see the folded table in ONE launch each; append and attention are
+launched per layer, in layer order, because in a model layer l+1's query depends on layer l's output.
+"""
+from typing import List, Optional
+
+import torch
+
+from . import binding as pe
+
+
+class LayeredCache:
+    def __init__(self, dtype, layers, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, layout, budget,
+                 device="cuda"):
+        self.layers, self.S = layers, num_seqs
+        self.Hk, self.Hq, self.D, self.B = num_kv_heads, num_q_heads, head_dim, block_size
+        self.dtype, self.budget, self.device = dtype, int(budget), device
+        R = layers * num_seqs
+        assert layout.block_table.shape[0] == R
+        self.folded = pe.PagedCache.create(dtype, R, num_kv_heads, num_q_heads, head_dim, block_size, layout, budget,
+                                           device)
+        f = self.folded
+        self.per_layer: List[pe.PagedCache] = []
+        for l in range(layers):
+            sl = slice(l * num_seqs, (l + 1) * num_seqs)
+            desc = pe.make_desc(dtype, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, layout.max_blocks,
+                                layout.num_phys_blocks)
+            c = pe.PagedCache(desc, f.k_pool, f.v_pool, f.block_table[sl], f.seq_lens[sl], f.spare[sl],
+                              f.spare_used[sl], f.freed_phys[sl], f.evicted_logical[sl], f.scores[sl], int(budget))
+            self.per_layer.append(c)
+        # one split workspace serves every layer: launches are ordered on one stream
+        self.decode_ws = pe.alloc_workspace(pe.PE_OP_PAGED_DECODE, self.per_layer[0].desc, device=device)
+        for c in self.per_layer:
+            c.decode_ws = self.decode_ws
+        self.host_lens = [0] * num_seqs   # the same in every layer
+
+    def prefill_prune_layer(self, layer, k_in, v_in, cu_seqlens, max_seqlen, kept_idx_out=None, workspace=None):
+        self.per_layer[layer].prefill_prune(k_in, v_in, cu_seqlens, max_seqlen, kept_idx_out, workspace)
+
+    def set_host_lens(self, prompt_lens):
+        self.host_lens = [min(int(L), self.budget) for L in prompt_lens]
+
+    def _triggers(self):
+        B, C = self.B, self.budget
+        return [n > 0 and n % B == 0 and n >= C for n in self.host_lens]
+
+    def decode_step(self, new_k, new_v, q, out, softmax_scale: Optional[float] = None, layer_hook=None):
+        """new_k, new_v [layers, S, Hk, D]; q, out [layers, S, Hq, D].  One decode iteration of all layers."""
+        trig = self._triggers()
+        if any(trig):
+            self.folded.score_blocks()
+            self.folded.evict_blocks()
+            self.host_lens = [n - self.B if t else n for n, t in zip(self.host_lens, trig)]
+        for l, c in enumerate(self.per_layer):
+            c.append_kv(new_k[l], new_v[l])
+            if layer_hook is not None:
+                layer_hook(l, 0)
+            c.paged_decode(q[l], out[l], softmax_scale)
+            if layer_hook is not None:
+                layer_hook(l, 1)
+        self.host_lens = [n + 1 for n in self.host_lens]
+        return any(trig)

@@ -1,0 +1,104 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects host-detectable
+misuse without launching anything (no GPU needed: every call below fails validation on the host)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2509_04377_amd import binding as pe
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "pe.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(pe_[a-z_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert set(names) == set(pe.EXPORTS), (names, pe.EXPORTS)
+    L = pe.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_status_strings():
+    assert pe.pe_version() >= 100
+    seen = {pe.status_string(s) for s in (0, -1, -2, -3, -4)}
+    assert len(seen) == 5 and pe.status_string(-99) == "unknown status"
+
+
+def _desc(**kw):
+    d = dict(dtype=pe.PE_BF16, num_seqs=4, num_kv_heads=8, num_q_heads=32, head_dim=128, block_size=16,
+             max_blocks=128, num_phys_blocks=4096)
+    d.update(kw)
+    return pe.make_desc(**d)
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(head_dim=96), pe.PE_ERR_UNSUPPORTED), (dict(block_size=8), pe.PE_ERR_UNSUPPORTED),
+    (dict(dtype=7), pe.PE_ERR_UNSUPPORTED), (dict(num_q_heads=30), pe.PE_ERR_INVALID_ARG),
+    (dict(num_q_heads=128), pe.PE_ERR_UNSUPPORTED), (dict(num_seqs=0), pe.PE_ERR_INVALID_ARG),
+    (dict(max_blocks=0), pe.PE_ERR_INVALID_ARG)])
+def test_bad_descriptors(kw, want):
+    d = _desc(**kw)
+    L = pe.lib()
+    assert L.pe_score_blocks(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None) == want
+    assert L.pe_evict_blocks(ctypes.byref(d), FAKE, FAKE, FAKE, 256, FAKE, FAKE, None) == want
+    assert L.pe_paged_decode(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, ctypes.c_float(0.1), FAKE, FAKE, 1 << 30,
+                             None) == want
+    assert pe.pe_workspace_bytes(pe.PE_OP_PAGED_DECODE, d) == 0
+
+
+def test_null_pointers_and_bad_budget():
+    d = _desc()
+    L = pe.lib()
+    assert L.pe_score_blocks(ctypes.byref(d), None, FAKE, FAKE, FAKE, FAKE, None, 0, None) == pe.PE_ERR_INVALID_ARG
+    assert L.pe_score_blocks(None, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None) == pe.PE_ERR_INVALID_ARG
+    assert L.pe_evict_blocks(ctypes.byref(d), FAKE, FAKE, None, 256, FAKE, FAKE, None) == pe.PE_ERR_INVALID_ARG
+    for bad in (0, -16, 250):
+        assert L.pe_evict_blocks(ctypes.byref(d), FAKE, FAKE, FAKE, bad, FAKE, FAKE, None) == pe.PE_ERR_INVALID_ARG
+        assert L.pe_prefill_prune(ctypes.byref(d), FAKE, FAKE, FAKE, 1000, 1000, bad, FAKE, FAKE, FAKE, FAKE, None,
+                                  FAKE, 1 << 30, None) == pe.PE_ERR_INVALID_ARG
+    assert L.pe_paged_decode(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, ctypes.c_float(float("nan")), FAKE, FAKE,
+                             1 << 30, None) == pe.PE_ERR_INVALID_ARG
+    assert L.pe_prefill_prune(ctypes.byref(d), FAKE, FAKE, FAKE, 1000, 2000, 256, FAKE, FAKE, FAKE, FAKE, None, FAKE,
+                              1 << 30, None) == pe.PE_ERR_INVALID_ARG   # max_seqlen > total_tokens
+    misaligned = ctypes.c_void_p(0x1004)
+    assert L.pe_score_blocks(ctypes.byref(d), misaligned, FAKE, FAKE, FAKE, FAKE, None, 0, None) == pe.PE_ERR_INVALID_ARG
+
+
+def test_workspace_checks():
+    d = _desc()
+    L = pe.lib()
+    need = pe.pe_workspace_bytes(pe.PE_OP_PREFILL_PRUNE, d, 4 * 1000)
+    assert need > 4 * 8 * 1000 * 4
+    args = (ctypes.byref(d), FAKE, FAKE, FAKE, 4000, 1000, 256, FAKE, FAKE, FAKE, FAKE, None)
+    assert L.pe_prefill_prune(*args, None, 0, None) == pe.PE_ERR_WORKSPACE
+    assert L.pe_prefill_prune(*args, FAKE, need - 1, None) == pe.PE_ERR_WORKSPACE
+    assert L.pe_prefill_prune(*args, ctypes.c_void_p(0x1010), need, None) == pe.PE_ERR_WORKSPACE   # misaligned
+    # decode: the split count (and with it the workspace) follows the option
+    pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, 1)
+    try:
+        assert pe.pe_workspace_bytes(pe.PE_OP_PAGED_DECODE, d) == 0
+        pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, 4)
+        w4 = pe.pe_workspace_bytes(pe.PE_OP_PAGED_DECODE, d)
+        assert w4 == 4 * 32 * 4 * (128 + 2) * 4
+        assert L.pe_paged_decode(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, ctypes.c_float(0.1), FAKE, FAKE,
+                                 w4 - 1, None) == pe.PE_ERR_WORKSPACE
+    finally:
+        pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, 0)
+    with pytest.raises(pe.PeError):
+        pe.pe_set_option(99, 1)
+    assert pe.pe_workspace_bytes(pe.PE_OP_SCORE_BLOCKS, d) == 0 and pe.pe_workspace_bytes(pe.PE_OP_EVICT_BLOCKS, d) == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(pe, "_lib", None)
+    monkeypatch.setattr(pe, "LIB_PATH", "/nonexistent/libpe.so")
+    with pytest.raises(RuntimeError, match="not built"):
+        pe.lib()

@@ -1,0 +1,201 @@
+"""GPU parity of the whole decode loop (prefill prune, then score + evict + append + attention per step)
+against the oracle's loop, on the benchmark's workloads: the tiny configuration in full, the Llama-shaped
+ones on subsets at their real per-row shape, and the headline shape at full size for one layer in the
+launch configuration the benchmark times."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle.decode_loop import decode_step as oracle_step
+from paper_2509_04377_amd import binding as pe
+from paper_2509_04377_amd import synth
+from paper_2509_04377_amd.engine import LayeredCache
+
+from _util import f32, i32, oracle_prefill, rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+SEED = 2024
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def _ulp(a, b):
+    return np.abs(a.view(np.int32).astype(np.int64) - b.view(np.int32).astype(np.int64))
+
+
+def _compare_state(cache_gpu, cache_cpu, where):
+    assert np.array_equal(cache_gpu.block_table.cpu().numpy(), cache_cpu.block_table), where
+    assert np.array_equal(cache_gpu.seq_lens.cpu().numpy(), cache_cpu.seq_lens), where
+    assert np.array_equal(cache_gpu.spare_used.cpu().numpy(), cache_cpu.spare_used), where
+
+
+def run_loop(wl, steps, layer=0, check_pool=True):
+    """One layer of workload `wl`: prune, then `steps` decode steps on both sides, compared every step."""
+    lens = synth.context_lengths(wl, SEED)
+    k_in, v_in, cu = synth.prompt_kv(wl, layer, lens, SEED)
+    layout = synth.page_layout(wl, lens, SEED, steps=steps)
+    ocache, okept, _ = oracle_prefill(wl, lens, k_in, v_in, cu, layout, wl.budget)
+
+    S, Hk, Hq, D, B = wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim, wl.block_size
+    gcache = pe.PagedCache.create(wl.torch_dtype, S, Hk, Hq, D, B, layout, wl.budget, DEV)
+    kept = torch.full((S, Hk, wl.budget), -9, dtype=torch.int32, device=DEV)
+    gcache.prefill_prune(k_in.to(DEV), v_in.to(DEV), cu.to(DEV), max(lens), kept)
+    gcache.set_host_lens(lens)
+    torch.cuda.synchronize()
+    assert np.array_equal(kept.cpu().numpy(), okept)
+    _compare_state(gcache, ocache, "after prune")
+    if check_pool:
+        assert np.array_equal(f32(gcache.k_pool).view(np.int32), ocache.k_pool.view(np.int32))
+        assert np.array_equal(f32(gcache.v_pool).view(np.int32), ocache.v_pool.view(np.int32))
+
+    out = torch.empty((S, Hq, D), dtype=wl.torch_dtype, device=DEV)
+    n_evictions, worst = 0, (0.0, 0.0)
+    for step in range(steps):
+        nk, nv, q = synth.decode_inputs(wl, layer, step, SEED)
+        triggered = gcache.any_trigger()
+        want, oscores, oev, ofr = oracle_step(ocache, f32(nk), f32(nv), f32(q))
+        gcache.evicted_logical.fill_(-1)
+        gcache.decode_step(nk.to(DEV), nv.to(DEV), q.to(DEV), out)
+        torch.cuda.synchronize()
+        where = "step %d" % step
+        _compare_state(gcache, ocache, where)
+        assert np.array_equal(gcache.evicted_logical.cpu().numpy(), oev), where
+        assert (oev >= 0).any() == triggered, where
+        if triggered:
+            n_evictions += 1
+            gs = gcache.scores.cpu().numpy()
+            assert np.array_equal(np.isinf(gs), np.isinf(oscores)), where
+            fin = np.isfinite(oscores)
+            assert _ulp(gs[fin], oscores[fin]).max() <= 1, where
+        e2, emax = rel_err(f32(out), want)
+        worst = (max(worst[0], e2), max(worst[1], emax))
+        assert e2 <= TOL[wl.dtype] and emax <= TOL[wl.dtype], (where, e2, emax)
+    assert gcache.host_lens == [int(x) for x in ocache.seq_lens]
+    if check_pool:
+        used = ocache.block_table[ocache.block_table >= 0]
+        gk, gv = f32(gcache.k_pool), f32(gcache.v_pool)
+        assert np.array_equal(gk[used].view(np.int32), ocache.k_pool[used].view(np.int32))
+        assert np.array_equal(gv[used].view(np.int32), ocache.v_pool[used].view(np.int32))
+    return n_evictions, worst
+
+
+def test_tiny_full():
+    """Configuration 1 in full: 512 -> 256 tokens, 32 steps, evictions at steps 1 and 17."""
+    print("case loop tiny_f32", flush=True)
+    n_ev, worst = run_loop(synth.TINY, synth.TINY.steps)
+    assert n_ev == 2
+    print("tiny worst attention error", worst, flush=True)
+
+
+def test_tiny_under_budget_growth():
+    print("case loop tiny under budget", flush=True)
+    wl = synth.TINY.with_(context=(40,), budget=64)
+    n_ev, _ = run_loop(wl, 60)
+    assert n_ev == 3
+
+
+def test_tiny_full_cache_never_evicts():
+    print("case loop tiny full cache", flush=True)
+    wl = synth.TINY.with_(budget=1024)
+    n_ev, _ = run_loop(wl, 32)
+    assert n_ev == 0
+
+
+@pytest.mark.parametrize("budget", [512, 1024, 2048])
+def test_llama32_1b_subset(budget):
+    """Configuration 2 shape (bf16, D=64, G=4), all 8 sequences of one layer, 36 steps (3 evictions)."""
+    print("case loop llama32_1b budget", budget, flush=True)
+    wl = synth.LLAMA32_1B.with_(budget=budget)
+    n_ev, worst = run_loop(wl, 36)
+    assert n_ev == 3
+    print("1b worst attention error", worst, flush=True)
+
+
+def test_llama32_3b_subset():
+    """Configuration 3 shape (bf16, D=128, G=3, ragged prompts, sink tokens): 5 sequences, 20 steps."""
+    print("case loop llama32_3b", flush=True)
+    wl = synth.LLAMA32_3B.with_(num_seqs=5)
+    n_ev, worst = run_loop(wl, 20, check_pool=False)
+    assert n_ev == 2
+    print("3b worst attention error", worst, flush=True)
+
+
+def test_llama31_8b_subset():
+    """Configuration 4 shape (bf16, D=128, G=4, shuffled shared pool): 3 sequences, 20 steps."""
+    print("case loop llama31_8b", flush=True)
+    wl = synth.LLAMA31_8B.with_(num_seqs=3)
+    n_ev, worst = run_loop(wl, 20, check_pool=False)
+    assert n_ev == 2
+    print("8b worst attention error", worst, flush=True)
+
+
+@pytest.mark.parametrize("B,C", [(16, 4096), (32, 8192)])
+def test_long_context_subset(B, C):
+    """Configuration 5 shape: one 65536-token prompt, budgets 4096 / 8192, page sizes 16 / 32."""
+    print("case loop long", B, C, flush=True)
+    wl = synth.LONG_8B.with_(num_seqs=1, block_size=B, budget=C)
+    n_ev, worst = run_loop(wl, B + 2, check_pool=False)
+    assert n_ev == 2
+    print("long worst attention error", worst, flush=True)
+
+
+def test_headline_full_size_one_layer_and_determinism():
+    """The headline shape at full size (32 sequences x 8 KV heads x 2048 tokens, bf16, shuffled pool), one
+    layer of the layered driver the benchmark uses, in the benchmark's launch configuration: every score,
+    every eviction decision, the whole table and every attention output against the oracle, for a trigger
+    step and a plain step; then the same step again from the same state must give identical bytes."""
+    print("case headline full size", flush=True)
+    wl = synth.LLAMA31_8B
+    layers = 2                                   # two layers share the pool; layer 1 is compared
+    S, Hk, Hq, D, B, C = wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim, wl.block_size, wl.budget
+    lens = [C] * S                               # the state right after the prune: every row at budget
+    layout = synth.page_layout(wl, lens * layers, SEED, steps=4)
+    eng = LayeredCache(wl.torch_dtype, layers, S, Hk, Hq, D, B, layout, C, DEV)
+    cu = torch.tensor(np.arange(S + 1) * C, dtype=torch.int32)
+    prompts = []
+    for l in range(layers):
+        k_in, v_in, _ = synth.prompt_kv(wl, l, lens, SEED)
+        eng.prefill_prune_layer(l, k_in.to(DEV), v_in.to(DEV), cu.to(DEV), C)
+        prompts.append((k_in, v_in))
+    eng.set_host_lens(lens)
+    torch.cuda.synchronize()
+    # oracle state for layer 1 (L == C: the prune is the identity copy)
+    l = 1
+    lay1 = synth.PageLayout(layout.block_table[l * S:(l + 1) * S], layout.spare[l * S:(l + 1) * S],
+                            layout.max_blocks, layout.n_spare, layout.num_phys_blocks)
+    ocache, _, _ = oracle_prefill(wl, lens, prompts[l][0], prompts[l][1], cu, lay1, C)
+    gl = eng.per_layer[l]
+    assert np.array_equal(gl.block_table.cpu().numpy(), ocache.block_table)
+
+    g = torch.Generator().manual_seed(SEED)
+    out = torch.empty((layers, S, Hq, D), dtype=wl.torch_dtype, device=DEV)
+    for step in range(2):                        # step 0 triggers (len == C), step 1 does not
+        nk = torch.randn((layers, S, Hk, D), generator=g).to(wl.torch_dtype)
+        nv = torch.randn((layers, S, Hk, D), generator=g).to(wl.torch_dtype)
+        q = torch.randn((layers, S, Hq, D), generator=g).to(wl.torch_dtype)
+        want, oscores, oev, ofr = oracle_step(ocache, f32(nk[l]), f32(nv[l]), f32(q[l]))
+        trig = eng.decode_step(nk.to(DEV), nv.to(DEV), q.to(DEV), out)
+        torch.cuda.synchronize()
+        assert trig == (step == 0)
+        assert np.array_equal(gl.block_table.cpu().numpy(), ocache.block_table)
+        assert np.array_equal(gl.seq_lens.cpu().numpy(), ocache.seq_lens)
+        if trig:
+            assert np.array_equal(gl.evicted_logical.cpu().numpy(), oev)
+            gs = gl.scores.cpu().numpy()
+            fin = np.isfinite(oscores)
+            assert np.array_equal(np.isinf(gs), np.isinf(oscores))
+            ulp = _ulp(gs[fin], oscores[fin])
+            assert ulp.max() <= 1
+            print("headline: %d scores, %d not bit-equal" % (fin.sum(), int((ulp != 0).sum())), flush=True)
+        e2, emax = rel_err(f32(out[l]), want)
+        print("headline step %d attention error %.3g %.3g" % (step, e2, emax), flush=True)
+        assert e2 <= 2e-2 and emax <= 2e-2
+    # determinism: the same attention launch twice gives identical bytes
+    qd = q.to(DEV)
+    o1 = torch.empty_like(out[l]); o2 = torch.empty_like(out[l])
+    gl.paged_decode(qd[l], o1)
+    gl.paged_decode(qd[l], o2)
+    torch.cuda.synchronize()
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)) and torch.equal(o1.view(torch.int16),
+                                                                                   out[l].view(torch.int16))

@@ -1,0 +1,288 @@
+"""GPU parity: each C-ABI call against the CPU oracle on the same seeded inputs, element by element.
+
+Bars: tables, lengths, eviction decisions, kept indices and pruned pool contents bit-exact; scores equal
+as fp32 up to one unit in the last place (both sides compute in fp64 and round once; only the order of
+fp64 additions differs); attention within 1e-5 (fp32) / 2e-2 (bf16) relative, per output vector, in the
+2-norm and in the max-norm.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_04377_amd import binding as pe
+
+from _util import f32, i32, rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+DTYPES = {"f32": torch.float32, "bf16": torch.bfloat16}
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def _ulp_diff(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """Distance in fp32 representable steps (inputs are non-negative floats or +inf)."""
+    return np.abs(a.view(np.int32).astype(np.int64) - b.view(np.int32).astype(np.int64))
+
+
+def make_paged(seed, lens, Hk, D, B, dtype, extra=1, pad_pages=3):
+    """Random rows in shuffled pages (torch CPU tensors in `dtype`); unused slots hold junk."""
+    g = torch.Generator().manual_seed(seed)
+    S = len(lens)
+    nb = [(L + B - 1) // B for L in lens]
+    mb = max(max(nb), 1) + extra
+    P = Hk * sum(nb) + pad_pages
+    ids = torch.randperm(P, generator=g).to(torch.int32)
+    table = torch.full((S, Hk, mb), -1, dtype=torch.int32)
+    pos = 0
+    for s in range(S):
+        for h in range(Hk):
+            table[s, h, :nb[s]] = ids[pos:pos + nb[s]]
+            pos += nb[s]
+    sc_k = torch.exp(0.5 * torch.randn((P, B, 1), generator=g))
+    sc_v = torch.exp(0.5 * torch.randn((P, B, 1), generator=g))
+    k_pool = (torch.randn((P, B, D), generator=g) * sc_k).to(dtype)
+    v_pool = (torch.randn((P, B, D), generator=g) * sc_v).to(dtype)
+    return k_pool, v_pool, table, torch.tensor(lens, dtype=torch.int32)
+
+
+def gpu_scores(k_pool, v_pool, table, lens, Hq=None):
+    P, B, D = k_pool.shape
+    S, Hk, mb = table.shape
+    desc = pe.make_desc(k_pool.dtype, S, Hk, Hq or Hk, D, B, mb, P)
+    out = torch.full((S, Hk, mb), -123.0, dtype=torch.float32, device=DEV)
+    pe.pe_score_blocks(desc, k_pool.to(DEV), v_pool.to(DEV), table.to(DEV), lens.to(DEV), out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("B", [16, 32])
+def test_score_blocks_random(dt, D, B):
+    print("case score_blocks_random", dt, D, B, flush=True)
+    # 37 pages per row at most: three 16-page groups with a ragged tail; a partial tail page; an empty row
+    lens = [37 * B, 20 * B + 5, 0, B, 16 * B]
+    k_pool, v_pool, table, sl = make_paged(100 + D + B, lens, 3, D, B, DTYPES[dt], extra=2)
+    got = gpu_scores(k_pool, v_pool, table, sl)
+    want = oracle.score_blocks(f32(k_pool), f32(v_pool), i32(table), i32(sl))
+    assert np.array_equal(np.isinf(got), np.isinf(want))
+    fin = np.isfinite(want)
+    ulp = _ulp_diff(got[fin], want[fin])
+    assert ulp.max() <= 1, "score differs by more than one fp32 step"
+    assert (ulp != 0).mean() < 1e-3, "scores should be bit-equal except at rare rounding boundaries"
+
+
+def test_score_blocks_closed_forms():
+    print("case score_blocks_closed_forms", flush=True)
+    B, D, Hk = 16, 128, 2
+    lens = [8 * B]
+    k_pool, v_pool, table, sl = make_paged(7, lens, Hk, D, B, torch.bfloat16)
+    # V = K  ->  exactly 1
+    got = gpu_scores(k_pool, k_pool.clone(), table, sl)
+    assert np.all(got[:, :, :8] == np.float32(1.0)) and np.all(np.isinf(got[:, :, 8:]))
+    # one-hot dyadic rows -> exact dyadic means; zero V row -> 0; zero K row -> +inf page
+    g = torch.Generator().manual_seed(8)
+    P = k_pool.shape[0]
+    ek = torch.randint(-3, 4, (P, B), generator=g)
+    ev = torch.randint(-3, 4, (P, B), generator=g)
+    k1 = torch.zeros((P, B, D)); v1 = torch.zeros((P, B, D))
+    col_k = torch.randint(0, D, (P, B), generator=g); col_v = torch.randint(0, D, (P, B), generator=g)
+    k1.scatter_(2, col_k[..., None], (2.0 ** ek)[..., None].float())
+    v1.scatter_(2, col_v[..., None], (2.0 ** ev)[..., None].float())
+    zero_v_page, zero_k_page = int(table[0, 0, 1]), int(table[0, 1, 2])
+    v1[zero_v_page, 3] = 0
+    k1[zero_k_page, 9] = 0
+    got = gpu_scores(k1.to(torch.bfloat16), v1.to(torch.bfloat16), table, sl)
+    want = oracle.score_blocks(k1.numpy(), v1.numpy(), i32(table), i32(sl))
+    assert np.array_equal(got.view(np.int32), want.view(np.int32))
+    ratio = (2.0 ** (ev - ek).double())
+    ratio[zero_v_page, 3] = 0
+    exact = ratio[int(table[0, 0, 1])].sum().item() / B
+    assert got[0, 0, 1] == np.float32(exact) and np.isinf(got[0, 1, 2])
+
+
+def test_evict_blocks_bit_exact():
+    print("case evict_blocks_bit_exact", flush=True)
+    rng = np.random.default_rng(300)
+    B, Hk = 16, 5
+    n_pages = [1, 2, 63, 64, 65, 128, 129, 300, 7, 40, 256, 0]
+    S = len(n_pages)
+    mb = 301
+    lens = np.array([n * B for n in n_pages], np.int32)
+    lens[8] -= 3            # tail not full -> no trigger
+    C = 2 * B               # sequence 0 (one page) is under budget
+    scores = rng.integers(0, 6, size=(S, Hk, mb)).astype(np.float32) * 0.25   # many exact ties
+    scores[5, 0, :] = 1.0                                                      # all-tie row -> page 0
+    scores[7, 1, 299] = -1.0                                                   # winner is the last page
+    scores[7, 2, 64] = -1.0                                                    # winner at a pass boundary
+    table = np.full((S, Hk, mb), -1, np.int32)
+    ids = rng.permutation(S * Hk * mb).astype(np.int32)
+    pos = 0
+    for s in range(S):
+        n = (lens[s] + B - 1) // B
+        for h in range(Hk):
+            table[s, h, :n] = ids[pos:pos + n]
+            pos += n
+    desc = pe.make_desc(torch.float32, S, Hk, Hk, 64, B, mb, S * Hk * mb)
+    t_gpu = torch.tensor(table, device=DEV)
+    l_gpu = torch.tensor(lens, device=DEV)
+    ev_gpu = torch.full((S, Hk), -7, dtype=torch.int32, device=DEV)
+    fr_gpu = torch.full((S, Hk), -7, dtype=torch.int32, device=DEV)
+    for call in range(3):   # three rounds: rows keep shrinking, winners move
+        ev, fr = oracle.evict_blocks(scores, table, lens, B, C)
+        pe.pe_evict_blocks(desc, torch.tensor(scores, device=DEV), t_gpu, l_gpu, C, ev_gpu, fr_gpu)
+        torch.cuda.synchronize()
+        assert np.array_equal(ev_gpu.cpu().numpy(), ev), call
+        assert np.array_equal(fr_gpu.cpu().numpy(), fr), call
+        assert np.array_equal(t_gpu.cpu().numpy(), table), call
+        assert np.array_equal(l_gpu.cpu().numpy(), lens), call
+    assert (ev >= 0).any() and (ev < 0).any()
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("D,B", [(64, 16), (128, 16), (64, 32), (128, 32)])
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 6, 8])
+def test_paged_decode_shapes(dt, D, B, G):
+    print("case paged_decode_shapes", dt, D, B, G, flush=True)
+    Hk = 2
+    lens = [0, 1, 15, 16, 17, 100, 700, 1300]
+    k_pool, v_pool, table, sl = make_paged(400 + D + B + G, lens, Hk, D, B, DTYPES[dt])
+    g = torch.Generator().manual_seed(401)
+    S, Hq = len(lens), Hk * G
+    q = torch.randn((S, Hq, D), generator=g).to(DTYPES[dt])
+    want = oracle.paged_decode(f32(q), f32(k_pool), f32(v_pool), i32(table), i32(sl))
+    P, mb = k_pool.shape[0], table.shape[2]
+    desc = pe.make_desc(DTYPES[dt], S, Hk, Hq, D, B, mb, P)
+    kd, vd, td, ld, qd = (x.to(DEV) for x in (k_pool, v_pool, table, sl, q))
+    try:
+        for splits in (0, 1, 3, 8):
+            pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, splits)
+            ws = pe.alloc_workspace(pe.PE_OP_PAGED_DECODE, desc)
+            out = torch.full((S, Hq, D), 7.0, dtype=DTYPES[dt], device=DEV)
+            pe.pe_paged_decode(desc, qd, kd, vd, td, ld, D ** -0.5, out, ws)
+            torch.cuda.synchronize()
+            got = f32(out)
+            assert np.all(got[0] == 0.0), "empty sequence must give zeros"
+            e2, emax = rel_err(got[1:], want[1:])
+            assert e2 <= TOL[dt] and emax <= TOL[dt], (splits, e2, emax)
+    finally:
+        pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, 0)
+
+
+def test_paged_decode_masks_junk_and_extreme_logits():
+    print("case paged_decode_masks_junk", flush=True)
+    Hk, G, D, B = 2, 4, 128, 16
+    lens = [21, 300]
+    k_pool, v_pool, table, sl = make_paged(500, lens, Hk, D, B, torch.float32)
+    # non-finite junk behind the end of every tail page must not leak in
+    for s, L in enumerate(lens):
+        for h in range(Hk):
+            p = int(table[s, h, L // B])
+            k_pool[p, L % B:] = float("nan")
+            v_pool[p, L % B:] = float("inf")
+    g = torch.Generator().manual_seed(501)
+    q = torch.randn((2, Hk * G, D), generator=g) * 6.0      # sharp softmax: large logit spread
+    want = oracle.paged_decode(f32(q), np.nan_to_num(f32(k_pool), nan=0.0, posinf=0.0),
+                               np.nan_to_num(f32(v_pool), nan=0.0, posinf=0.0), i32(table), i32(sl))
+    desc = pe.make_desc(torch.float32, 2, Hk, Hk * G, D, B, table.shape[2], k_pool.shape[0])
+    out = torch.empty((2, Hk * G, D), dtype=torch.float32, device=DEV)
+    ws = pe.alloc_workspace(pe.PE_OP_PAGED_DECODE, desc)
+    pe.pe_paged_decode(desc, q.to(DEV), k_pool.to(DEV), v_pool.to(DEV), table.to(DEV), sl.to(DEV), D ** -0.5, out, ws)
+    torch.cuda.synchronize()
+    got = f32(out)
+    assert np.all(np.isfinite(got))
+    e2, emax = rel_err(got, want)
+    assert e2 <= 1e-5 and emax <= 1e-5, (e2, emax)
+
+
+def _prompt(seed, lens, Hk, D, dtype, ties=False):
+    g = torch.Generator().manual_seed(seed)
+    T = sum(lens)
+    k = (torch.randn((T, Hk, D), generator=g) * torch.exp(0.5 * torch.randn((T, Hk, 1), generator=g))).to(dtype)
+    v = (torch.randn((T, Hk, D), generator=g) * torch.exp(0.5 * torch.randn((T, Hk, 1), generator=g))).to(dtype)
+    if ties:   # repeat a handful of rows many times: exact score ties, also at the cut
+        src = torch.randint(0, T, (T,), generator=g) % 7
+        k, v = k[src].contiguous(), v[src].contiguous()
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32)
+    return k, v, cu
+
+
+def _prune_both(k, v, cu, lens, Hk, D, B, C, dtype, seed):
+    S = len(lens)
+    need = [(min(L, C) + B - 1) // B for L in lens]
+    mb = max(max(need), 1) + 1
+    P = Hk * sum(need) + 2
+    ids = torch.randperm(P, generator=torch.Generator().manual_seed(seed)).to(torch.int32)
+    table = torch.full((S, Hk, mb), -1, dtype=torch.int32)
+    pos = 0
+    for s in range(S):
+        for h in range(Hk):
+            table[s, h, :need[s]] = ids[pos:pos + need[s]]
+            pos += need[s]
+    kp = np.zeros((P, B, D), np.float32); vp = np.zeros((P, B, D), np.float32)
+    o_lens, o_kept = oracle.prefill_prune(f32(k), f32(v), i32(cu), C, kp, vp, i32(table))
+    desc = pe.make_desc(dtype, S, Hk, Hk, D, B, mb, P)
+    kpd = torch.zeros((P, B, D), dtype=dtype, device=DEV); vpd = torch.zeros((P, B, D), dtype=dtype, device=DEV)
+    lens_d = torch.full((S,), -5, dtype=torch.int32, device=DEV)
+    kept_d = torch.full((S, Hk, C), -9, dtype=torch.int32, device=DEV)
+    ws = pe.alloc_workspace(pe.PE_OP_PREFILL_PRUNE, desc, int(cu[-1]))
+    pe.pe_prefill_prune(desc, k.to(DEV), v.to(DEV), cu.to(DEV), int(cu[-1]), max(lens), C, kpd, vpd, table.to(DEV),
+                        lens_d, kept_d, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(lens_d.cpu().numpy(), o_lens)
+    assert np.array_equal(kept_d.cpu().numpy(), o_kept)
+    # pool contents: every slot the oracle wrote (the rest stayed zero on both sides)
+    assert np.array_equal(f32(kpd).view(np.int32), kp.view(np.int32))
+    assert np.array_equal(f32(vpd).view(np.int32), vp.view(np.int32))
+    return o_kept
+
+
+@pytest.mark.parametrize("dt,D", [("f32", 64), ("bf16", 64), ("bf16", 128), ("f32", 128)])
+def test_prefill_prune_ragged(dt, D):
+    print("case prefill_prune_ragged", dt, D, flush=True)
+    lens = [1, 100, 1023, 1024, 1025, 3000, 5000, 256]
+    for C, B in ((256, 16), (1024, 32)):
+        k, v, cu = _prompt(600 + D + C, lens, 2, D, DTYPES[dt])
+        _prune_both(k, v, cu, lens, 2, D, B, C, DTYPES[dt], 601)
+
+
+def test_prefill_prune_ties():
+    print("case prefill_prune_ties", flush=True)
+    lens = [2100, 700]
+    k, v, cu = _prompt(610, lens, 2, 128, torch.bfloat16, ties=True)
+    kept = _prune_both(k, v, cu, lens, 2, 128, 16, 512, torch.bfloat16, 611)
+    assert kept.max() > 0
+    # V = K: every score is exactly 1 -> the E lowest indices go
+    kept = _prune_both(k, k.clone(), cu, lens, 2, 128, 16, 512, torch.bfloat16, 612)
+    assert np.array_equal(kept[0, 0], np.arange(2100 - 512, 2100))
+
+
+def test_append_kv_matches_oracle():
+    print("case append_kv", flush=True)
+    Hk, D, B = 3, 64, 16
+    lens = [16, 5, 0, 31, 32]
+    k_pool, v_pool, table, sl = make_paged(700, lens, Hk, D, B, torch.bfloat16, extra=2, pad_pages=40)
+    S, mb, P = len(lens), table.shape[2], k_pool.shape[0]
+    used = set(int(x) for x in table.flatten() if x >= 0)
+    free = [p for p in range(P) if p not in used]
+    n_spare = 2
+    spare = torch.tensor(free[:S * Hk * n_spare], dtype=torch.int32).reshape(S, Hk, n_spare)
+    freed = torch.full((S, Hk), -1, dtype=torch.int32)
+    freed[0, 1] = free[-1]                         # one row re-uses a page it "just freed"
+    spare_used = torch.zeros((S, Hk), dtype=torch.int32)
+    o = dict(k=f32(k_pool), v=f32(v_pool), t=i32(table).copy(), l=i32(sl).copy(), f=i32(freed).copy(),
+             u=i32(spare_used).copy())
+    desc = pe.make_desc(torch.bfloat16, S, Hk, Hk, D, B, mb, P)
+    kd, vd, td, ld, fd, sd, ud = (x.to(DEV) for x in (k_pool, v_pool, table, sl, freed, spare, spare_used))
+    g = torch.Generator().manual_seed(701)
+    for step in range(3):
+        nk = torch.randn((S, Hk, D), generator=g).to(torch.bfloat16)
+        nv = torch.randn((S, Hk, D), generator=g).to(torch.bfloat16)
+        oracle.append_kv(f32(nk), f32(nv), o["k"], o["v"], o["t"], o["l"], o["f"], i32(spare), o["u"])
+        pe.pe_append_kv(desc, nk.to(DEV), nv.to(DEV), kd, vd, td, ld, fd, sd, ud)
+        torch.cuda.synchronize()
+        assert np.array_equal(td.cpu().numpy(), o["t"]) and np.array_equal(ld.cpu().numpy(), o["l"])
+        assert np.array_equal(fd.cpu().numpy(), o["f"]) and np.array_equal(ud.cpu().numpy(), o["u"])
+        assert np.array_equal(f32(kd).view(np.int32), o["k"].view(np.int32))
+        assert np.array_equal(f32(vd).view(np.int32), o["v"].view(np.int32))
