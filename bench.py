@@ -1,0 +1,245 @@
+#!/usr/bin/env python3
+"""Decode throughput of the PagedEviction hot path (score + evict + paged attention) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama31_8b]
+
+A step is one decode iteration of ALL layers over the whole batch: on steps where the newest page of
+the sequences has just filled at budget, one block-score sweep and one eviction over all layers (layers
+folded into the sequence dimension), then per layer the append of the new token and the paged attention,
+back to back on one stream.  K/V pools, tables and the per-step inputs are resident in HBM before the
+timed region.  Prints ONE JSON line (see the design doc for the fields' derivations).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="llama31_8b")
+    ap.add_argument("--budget", type=int, default=None)
+    ap.add_argument("--seed", type=int, default=2509)
+    ap.add_argument("--splits", type=int, default=None, help="override the split count of pe_paged_decode")
+    ap.add_argument("--xcd-map", type=int, default=None, choices=(0, 1))
+    ap.add_argument("--sample-every", type=int, default=8, help="time the attention launches of every n-th step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=8)
+    ap.add_argument("--cpu-layers", type=int, default=2)
+    ap.add_argument("--cpu-steps", type=int, default=17)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference dispatch for rocprofv3 --pmc scaling)")
+    return ap.parse_args()
+
+
+def traffic_from_profiles(workload):
+    """HBM bytes per attention launch measured with rocprofv3 --pmc, if a summary is committed."""
+    path = os.path.join(ROOT, "profiles", "paged_decode_%s_pmc.md" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def build_engine(wl, seed, dev):
+    import torch
+    from paper_2509_04377_amd import binding as pe
+    from paper_2509_04377_amd import synth
+    from paper_2509_04377_amd.engine import LayeredCache
+
+    lens = synth.context_lengths(wl, seed)
+    layout = synth.page_layout(wl, lens * wl.layers, seed)
+    eng = LayeredCache(wl.torch_dtype, wl.layers, wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim,
+                       wl.block_size, layout, wl.budget, dev)
+    total = sum(lens)
+    ws = pe.alloc_workspace(pe.PE_OP_PREFILL_PRUNE, eng.per_layer[0].desc, total, device=dev)
+    prune_ms = []
+    for l in range(wl.layers):
+        k_in, v_in, cu = synth.prompt_kv(wl, l, lens, seed, device=dev)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        eng.prefill_prune_layer(l, k_in, v_in, cu, max(lens), None, ws)
+        torch.cuda.synchronize()
+        prune_ms.append((time.perf_counter() - t0) * 1e3)
+        del k_in, v_in
+    eng.set_host_lens(lens)
+    elem = 2 if wl.dtype == "bf16" else 4
+    prune_bytes = 2 * total * wl.num_kv_heads * wl.head_dim * elem      # K and V sweep of one layer
+    return eng, lens, prune_ms, prune_bytes
+
+
+def cpu_baseline(wl, seed, n_seqs, n_layers, steps):
+    """The oracle, as it stands, on a bounded sample of the same workload: `n_seqs` sequences of `n_layers`
+    layers, prune (untimed) then `steps` decode steps (timed).  Scaled to whole-model tokens/s."""
+    import numpy as np
+    import torch
+    import oracle
+    from oracle.decode_loop import OracleCache, decode_step
+    from paper_2509_04377_amd import synth
+
+    sub = wl.with_(num_seqs=min(n_seqs, wl.num_seqs))
+    lens = synth.context_lengths(sub, seed)
+    S, Hk, B, D = sub.num_seqs, sub.num_kv_heads, sub.block_size, sub.head_dim
+
+    def np32(t):
+        return t.to(torch.float32).contiguous().numpy()
+
+    caches = []
+    for l in range(n_layers):
+        k_in, v_in, cu = synth.prompt_kv(sub, l, lens, seed)
+        layout = synth.page_layout(sub, lens, seed, steps=steps)
+        kp = np.zeros((layout.num_phys_blocks, B, D), np.float32)
+        vp = np.zeros_like(kp)
+        table = layout.block_table.numpy().copy()
+        o_lens, _ = oracle.prefill_prune(np32(k_in), np32(v_in), cu.numpy(), sub.budget, kp, vp, table)
+        caches.append(OracleCache(kp, vp, table, o_lens, layout.spare.numpy().copy(), np.zeros((S, Hk), np.int32),
+                                  np.full((S, Hk), -1, np.int32), sub.budget))
+        del k_in, v_in
+    inputs = [[tuple(np32(x) for x in synth.decode_inputs(sub, l, st, seed)) for l in range(n_layers)]
+              for st in range(steps)]
+    t0 = time.perf_counter()
+    for st in range(steps):
+        for l in range(n_layers):
+            nk, nv, q = inputs[st][l]
+            decode_step(caches[l], nk, nv, q)
+    dt = time.perf_counter() - t0
+    per_layer_step = dt / (steps * n_layers)                  # one layer, S sequences, one step
+    tokens_per_s = S / (per_layer_step * wl.layers)
+    return {"value": tokens_per_s, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d of %d sequences x %d of %d layers x %d consecutive decode steps from the pruned state "
+                      "(evictions at steps 1 and 17), %.1f s wall; scaled to all layers"
+                      % (S, wl.num_seqs, n_layers, wl.layers, steps, dt),
+            "ms_per_layer_step": per_layer_step * 1e3}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards with no collective; see DESIGN.md); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2509_04377_amd import binding as pe
+    from paper_2509_04377_amd import synth
+
+    wl = synth.WORKLOADS[args.workload]
+    if args.budget is not None:
+        wl = wl.with_(budget=args.budget)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    if args.splits is not None:
+        pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, args.splits)
+    if args.xcd_map is not None:
+        pe.pe_set_option(pe.PE_OPT_DECODE_XCD_MAP, args.xcd_map)
+
+    eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev)
+    L, S, Hk, Hq, D = wl.layers, wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim
+    elem = 2 if wl.dtype == "bf16" else 4
+
+    # a short ring of per-step inputs, resident before the timed region
+    ring = 4
+    g = torch.Generator(device=dev)
+    g.manual_seed(args.seed + 99)
+    new_k = (torch.randn((ring, L, S, Hk, D), generator=g, device=dev) *
+             torch.exp(0.5 * torch.randn((ring, L, S, Hk, 1), generator=g, device=dev))).to(wl.torch_dtype)
+    new_v = (torch.randn((ring, L, S, Hk, D), generator=g, device=dev) *
+             torch.exp(0.5 * torch.randn((ring, L, S, Hk, 1), generator=g, device=dev))).to(wl.torch_dtype)
+    q = torch.randn((ring, L, S, Hq, D), generator=g, device=dev).to(wl.torch_dtype)
+    out = torch.empty((L, S, Hq, D), dtype=wl.torch_dtype, device=dev)
+
+    for st in range(args.warmup):
+        eng.decode_step(new_k[st % ring], new_v[st % ring], q[st % ring], out)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly --steps steps ---------------------------------------------------------
+    samples = []          # (event_start, event_end, algorithmic bytes) per sampled attention launch
+    state = {}
+
+    def hook(layer, phase):
+        if phase == 0:
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()
+            state["e0"] = e
+        else:
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()
+            cached = sum(eng.host_lens) + S          # host_lens is bumped after the layer loop
+            samples.append((state["e0"], e, cached * Hk * D * 2 * elem))
+
+    step_events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    n_trigger = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    step_events[0].record()
+    for st in range(args.steps):
+        i = (args.warmup + st) % ring
+        sampled = args.sample_every > 0 and st % args.sample_every == args.sample_every // 2
+        n_trigger += bool(eng.decode_step(new_k[i], new_v[i], q[i], out, None, hook if sampled else None))
+        step_events[st + 1].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    # ---------------------------------------------------------------------------------------------------
+
+    step_ms = sorted(step_events[i].elapsed_time(step_events[i + 1]) for i in range(args.steps))
+    tokens_per_s = S * args.steps / elapsed
+    result = {
+        "metric": "decode tokens/s (score+evict+paged attn), %s shape" % wl.name,
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": "%s: %d layers, %d seqs x %d KV heads (%d q heads), head_dim %d, page %d, context %s -> "
+                               "budget %d" % (wl.name, L, S, Hk, Hq, D, wl.block_size, "/".join(map(str, wl.context)),
+                                              wl.budget),
+                   "decode_splits": pe.pe_get_option(pe.PE_OPT_DECODE_SPLITS),
+                   "trigger_steps": n_trigger},
+        "step_ms": {"p50": step_ms[len(step_ms) // 2], "p99": step_ms[min(len(step_ms) - 1, int(len(step_ms) * 0.99))],
+                    "max": step_ms[-1]},
+        "prefill_prune": {"ms_per_layer": sorted(prune_ms)[len(prune_ms) // 2],
+                          "sweep_GBps": prune_bytes / (sorted(prune_ms)[len(prune_ms) // 2] * 1e-3) / 1e9},
+    }
+    if samples:
+        durs = [a.elapsed_time(b) * 1e-3 for a, b, _ in samples]
+        avg_dur = sum(durs) / len(durs)
+        avg_bytes = sum(nb for _, _, nb in samples) / len(samples)
+        achieved = avg_bytes / avg_dur / 1e9
+        result["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(wl.name),
+                              "kernel": "paged_decode_kernel (+ split reduce)", "launches_timed": len(samples),
+                              "avg_launch_us": avg_dur * 1e6, "algorithmic_bytes_per_launch": avg_bytes}
+    # whole-step algorithmic bytes: attention every step + the score sweep on trigger steps
+    att_bytes = L * Hk * D * 2 * elem * (sum(eng.host_lens) - S * args.steps / 2.0)   # rough mean over the run
+    result["path_GBps"] = None
+    if samples:
+        mean_cached = sum(nb for _, _, nb in samples) / len(samples)        # per layer
+        score_bytes = L * S * Hk * (wl.budget // wl.block_size) * wl.block_size * D * 2 * elem
+        total_bytes = mean_cached * L * args.steps + score_bytes * n_trigger
+        result["path_GBps"] = total_bytes / elapsed / 1e9
+        result["path_frac_of_hbm_peak"] = result["path_GBps"] / HBM_PEAK_GBS
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, args.seed, args.cpu_seqs, args.cpu_layers, args.cpu_steps)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -31,9 +31,18 @@ class OracleCache:
 
 
 def decode_step(cache: OracleCache, new_k, new_v, q, scale=None):
-    """Runs (i)-(iii) in place on `cache`.  Returns (out fp64, scores, evicted_logical, freed_phys)."""
-    scores = score_blocks(cache.k_pool, cache.v_pool, cache.block_table, cache.seq_lens)
-    evicted, freed = evict_blocks(scores, cache.block_table, cache.seq_lens, cache.block_size, cache.budget)
+    """Runs (i)-(iii) in place on `cache`.  Returns (out fp64, scores, evicted_logical, freed_phys);
+    scores is None on a step where no sequence's newest page has just filled at budget (Alg. 3 scores
+    pages only inside its "L % B == 0" branch)."""
+    B, C = cache.block_size, cache.budget
+    lens = cache.seq_lens
+    if np.any((lens > 0) & (lens % B == 0) & (lens >= C)):
+        scores = score_blocks(cache.k_pool, cache.v_pool, cache.block_table, cache.seq_lens)
+        evicted, freed = evict_blocks(scores, cache.block_table, cache.seq_lens, B, C)
+    else:
+        scores = None
+        evicted = np.full(cache.freed_phys.shape, -1, np.int32)
+        freed = np.full(cache.freed_phys.shape, -1, np.int32)
     freed_report = freed.copy()
     cache.freed_phys[...] = freed
     append_kv(new_k, new_v, cache.k_pool, cache.v_pool, cache.block_table, cache.seq_lens,
