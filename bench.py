@@ -32,7 +32,10 @@ def parse_args():
     ap.add_argument("--seed", type=int, default=2509)
     ap.add_argument("--splits", type=int, default=None, help="override the split count of pe_paged_decode")
     ap.add_argument("--xcd-map", type=int, default=None, choices=(0, 1))
+    ap.add_argument("--waves", type=int, default=None)
+    ap.add_argument("--depth", type=int, default=None)
     ap.add_argument("--sample-every", type=int, default=8, help="time the attention launches of every n-th step")
+    ap.add_argument("--unfused", action="store_true", help="separate append and attention launches per layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=8)
     ap.add_argument("--cpu-layers", type=int, default=2)
@@ -144,8 +147,13 @@ def main():
         pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, args.splits)
     if args.xcd_map is not None:
         pe.pe_set_option(pe.PE_OPT_DECODE_XCD_MAP, args.xcd_map)
+    if args.waves is not None:
+        pe.pe_set_option(pe.PE_OPT_DECODE_WAVES, args.waves)
+    if args.depth is not None:
+        pe.pe_set_option(pe.PE_OPT_DECODE_DEPTH, args.depth)
 
     eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev)
+    eng.fused = not args.unfused
     L, S, Hk, Hq, D = wl.layers, wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim
     elem = 2 if wl.dtype == "bf16" else 4
 
@@ -203,7 +211,7 @@ def main():
         "config": {"workload": "%s: %d layers, %d seqs x %d KV heads (%d q heads), head_dim %d, page %d, context %s -> "
                                "budget %d" % (wl.name, L, S, Hk, Hq, D, wl.block_size, "/".join(map(str, wl.context)),
                                               wl.budget),
-                   "decode_splits": pe.pe_get_option(pe.PE_OPT_DECODE_SPLITS),
+                   "decode_splits": pe.pe_get_option(pe.PE_OPT_DECODE_SPLITS), "fused_append": eng.fused,
                    "trigger_steps": n_trigger},
         "step_ms": {"p50": step_ms[len(step_ms) // 2], "p99": step_ms[min(len(step_ms) - 1, int(len(step_ms) * 0.99))],
                     "max": step_ms[-1]},
@@ -217,7 +225,7 @@ def main():
         achieved = avg_bytes / avg_dur / 1e9
         result["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(wl.name),
-                              "kernel": "paged_decode_kernel (+ split reduce)", "launches_timed": len(samples),
+                              "kernel": "paged_decode_kernel", "launches_timed": len(samples),
                               "avg_launch_us": avg_dur * 1e6, "algorithmic_bytes_per_launch": avg_bytes}
     # whole-step algorithmic bytes: attention every step + the score sweep on trigger steps
     att_bytes = L * Hk * D * 2 * elem * (sum(eng.host_lens) - S * args.steps / 2.0)   # rough mean over the run

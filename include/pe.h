@@ -55,7 +55,8 @@ typedef enum {
   PE_OP_SCORE_BLOCKS = 0,
   PE_OP_PREFILL_PRUNE = 1,
   PE_OP_EVICT_BLOCKS = 2,
-  PE_OP_PAGED_DECODE = 3
+  PE_OP_PAGED_DECODE = 3,
+  PE_OP_APPEND_PAGED_DECODE = 4
 } pe_op;
 
 typedef struct pe_cache_desc {
@@ -83,7 +84,8 @@ int pe_version(void);
 /* Tuning knobs (host side, process wide, not thread safe).  key PE_OPT_DECODE_SPLITS: number of
  * splits of a row in pe_paged_decode (0 = choose from the shape).  Returns PE_OK or
  * PE_ERR_INVALID_ARG.  pe_workspace_bytes() follows the current setting. */
-enum { PE_OPT_DECODE_SPLITS = 0, PE_OPT_DECODE_XCD_MAP = 1, PE_OPT_COUNT_ = 2 };
+enum { PE_OPT_DECODE_SPLITS = 0, PE_OPT_DECODE_XCD_MAP = 1, PE_OPT_DECODE_WAVES = 2, PE_OPT_DECODE_DEPTH = 3,
+       PE_OPT_COUNT_ = 4 };
 int pe_set_option(int key, int value);
 int pe_get_option(int key);
 
@@ -158,6 +160,21 @@ int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool
 int pe_append_kv(const pe_cache_desc* desc, const void* new_k, const void* new_v, void* k_pool, void* v_pool,
                  int32_t* block_table, int32_t* seq_lens, int32_t* freed_phys, const int32_t* spare,
                  int32_t* spare_used, int32_t n_spare, void* stream);
+
+/*
+ * The two calls above in ONE launch: exactly the effect of pe_append_kv followed by pe_paged_decode
+ * (Alg. 3: the new token joins the cache, then "PagedAttention(Q,K,V)" over everything cached), i.e.
+ * attention over the seq_lens[s] cached tokens plus the new token, the new K/V rows stored into the
+ * tail page (a new page linked in first when seq_lens[s] % B == 0), seq_lens[s] += 1.  The new rows
+ * are attended to from registers instead of being read back from the pool.
+ * workspace: pe_workspace_bytes(PE_OP_APPEND_PAGED_DECODE, desc, 0).  Its leading
+ * ((4*S + 255) & ~255) bytes hold per-sequence arrival counters: they must be ZERO before the first
+ * call that uses this workspace (e.g. hipMemsetAsync once) and every call leaves them zero.
+ */
+int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const void* new_v, const void* q,
+                           void* k_pool, void* v_pool, int32_t* block_table, int32_t* seq_lens, int32_t* freed_phys,
+                           const int32_t* spare, int32_t* spare_used, int32_t n_spare, float softmax_scale, void* out,
+                           void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -18,10 +18,12 @@ PE_OK = 0
 PE_ERR_INVALID_ARG, PE_ERR_UNSUPPORTED, PE_ERR_WORKSPACE, PE_ERR_HIP = -1, -2, -3, -4
 PE_F32, PE_BF16 = 0, 1
 PE_OP_SCORE_BLOCKS, PE_OP_PREFILL_PRUNE, PE_OP_EVICT_BLOCKS, PE_OP_PAGED_DECODE = 0, 1, 2, 3
-PE_OPT_DECODE_SPLITS, PE_OPT_DECODE_XCD_MAP = 0, 1
+PE_OP_APPEND_PAGED_DECODE = 4
+PE_OPT_DECODE_SPLITS, PE_OPT_DECODE_XCD_MAP, PE_OPT_DECODE_WAVES, PE_OPT_DECODE_DEPTH = 0, 1, 2, 3
 
 EXPORTS = ["pe_workspace_bytes", "pe_status_string", "pe_version", "pe_set_option", "pe_get_option",
-           "pe_score_blocks", "pe_prefill_prune", "pe_evict_blocks", "pe_paged_decode", "pe_append_kv"]
+           "pe_score_blocks", "pe_prefill_prune", "pe_evict_blocks", "pe_paged_decode", "pe_append_kv",
+           "pe_append_paged_decode"]
 
 
 class pe_cache_desc(ctypes.Structure):
@@ -69,6 +71,8 @@ def lib():
         L.pe_paged_decode.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
         L.pe_append_kv.restype = ctypes.c_int
         L.pe_append_kv.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
+        L.pe_append_paged_decode.restype = ctypes.c_int
+        L.pe_append_paged_decode.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ctypes.c_float, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -177,6 +181,25 @@ def pe_append_kv(desc, new_k, new_v, k_pool, v_pool, block_table, seq_lens, free
                               int(spare.shape[-1]), _stream()), "pe_append_kv")
 
 
+def pe_append_paged_decode(desc, new_k, new_v, q, k_pool, v_pool, block_table, seq_lens, freed_phys, spare, spare_used,
+                           softmax_scale, out, workspace):
+    wp, wn = _ws(workspace)
+    _check(lib().pe_append_paged_decode(ctypes.byref(desc), _ptr(new_k, "new_k"), _ptr(new_v, "new_v"), _ptr(q, "q"),
+                                        _ptr(k_pool, "k_pool"), _ptr(v_pool, "v_pool"),
+                                        _ptr(block_table, "block_table", torch.int32),
+                                        _ptr(seq_lens, "seq_lens", torch.int32),
+                                        _ptr(freed_phys, "freed_phys", torch.int32), _ptr(spare, "spare", torch.int32),
+                                        _ptr(spare_used, "spare_used", torch.int32), int(spare.shape[-1]),
+                                        ctypes.c_float(softmax_scale), _ptr(out, "out"), wp, wn, _stream()),
+           "pe_append_paged_decode")
+
+
+def alloc_zeroed_workspace(op: int, desc: pe_cache_desc, device="cuda"):
+    """Workspace for calls that keep arrival counters in it: zero-filled once, left zero by every call."""
+    n = pe_workspace_bytes(op, desc, 0)
+    return torch.zeros((n + 255) // 256 * 256, dtype=torch.uint8, device=device)
+
+
 @dataclass
 class PagedCache:
     """Device-side state of one paged KV cache (one layer, or several layers folded into num_seqs).
@@ -195,6 +218,7 @@ class PagedCache:
     budget: int
     decode_ws: torch.Tensor = None
     host_lens: list = None     # host mirror of seq_lens (pure integer bookkeeping, never read back)
+    fused_ws: torch.Tensor = None  # workspace of pe_append_paged_decode (arrival counters + split partials)
 
     @staticmethod
     def create(dtype, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, layout, budget, device="cuda",
@@ -231,7 +255,15 @@ class PagedCache:
         B = self.desc.block_size
         return any(n > 0 and n % B == 0 and n >= self.budget for n in self.host_lens)
 
-    def decode_step(self, new_k, new_v, q, out, softmax_scale=None):
+    def append_paged_decode(self, new_k, new_v, q, out, softmax_scale=None):
+        if softmax_scale is None:
+            softmax_scale = float(self.desc.head_dim) ** -0.5
+        if self.fused_ws is None:
+            self.fused_ws = alloc_zeroed_workspace(PE_OP_APPEND_PAGED_DECODE, self.desc, device=q.device)
+        pe_append_paged_decode(self.desc, new_k, new_v, q, self.k_pool, self.v_pool, self.block_table, self.seq_lens,
+                               self.freed_phys, self.spare, self.spare_used, softmax_scale, out, self.fused_ws)
+
+    def decode_step(self, new_k, new_v, q, out, softmax_scale=None, fused=True):
         """One decode iteration of one layer (Alg. 3): score + evict when some sequence's newest page has
         filled at budget, append the new token, attend.  Which steps trigger follows from the lengths
         alone, so the host decides it without reading anything back."""
@@ -240,9 +272,12 @@ class PagedCache:
             self.score_blocks()
             self.evict_blocks()
             self.host_lens = [n - B if (n > 0 and n % B == 0 and n >= self.budget) else n for n in self.host_lens]
-        self.append_kv(new_k, new_v)
+        if fused:
+            self.append_paged_decode(new_k, new_v, q, out, softmax_scale)
+        else:
+            self.append_kv(new_k, new_v)
+            self.paged_decode(q, out, softmax_scale)
         self.host_lens = [n + 1 for n in self.host_lens]
-        self.paged_decode(q, out, softmax_scale)
 
     def score_blocks(self):
         pe_score_blocks(self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, self.scores)

@@ -16,14 +16,17 @@
 // At the end the (wave, token-stream) partial states are merged through LDS; with one split the
 // workgroup writes the normalised output, otherwise it writes (acc, m, l) partials that
 // paged_decode_reduce_kernel merges.
+//
+// The FUSED variant also performs the harness append of the same decode iteration: the new token's K/V
+// rows are taken from registers as one extra token of the row (they are not read back from the pool),
+// the last split's workgroup links a new page if the tail page is full and stores the rows into the
+// pool, and the workgroup that arrives last at a per-sequence counter bumps seq_lens.
 #include "pe_device.h"
 #include "pe_launch.h"
 
 namespace pe {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / kWave;
 constexpr int kLoadsPerTile = 4;
 constexpr float kNegInf = -__builtin_inff();
 
@@ -147,6 +150,14 @@ struct DecodeParams {
   float* partials;
   float scale_log2e;
   int num_kv_heads, num_q_heads, max_blocks, log2_block, splits, xcd_map, g_real;
+  // fused append (FUSED kernels only)
+  const void* new_k;
+  const void* new_v;
+  int32_t* freed_phys;
+  const int32_t* spare;
+  int32_t* spare_used;
+  int32_t* seq_counter;  // [S], zero between launches
+  int n_spare;
 };
 
 template <typename T, int D, int G>
@@ -160,32 +171,52 @@ struct Tile {
   static constexpr int GP = next_pow2(G);
   static_assert(GP <= LPR && GP <= 8, "query group too large");
 
-  // Issue the 2*NLT wave-loads of tile `tile`.  A load whose first token lies beyond the last page is
-  // redirected to the last page (its tokens are masked later), so every address is inside the pool.
-  static __device__ __forceinline__ void issue(uint4 (&kb)[NLT], uint4 (&vb)[NLT], int tile, const T* k_pool,
-                                               const T* v_pool, const int32_t* bt, int npages, int log2_block,
-                                               int lane) {
+  // A tile touches at most NPT pages (two when a 32-token tile meets 16-token pages).
+  static constexpr int NPT = TT > 16 ? TT / 16 : 1;
+
+  // Scalar loads of the physical page ids of tile `tile`.  Entries beyond the row's last page are
+  // redirected to the last page (their tokens are masked later), so every address stays inside the pool.
+  static __device__ __forceinline__ void lookup(int (&phys)[NPT], int tile, const int32_t* bt, int npages,
+                                                int log2_block) {
+    const int p0 = (tile * TT) >> log2_block;
+#pragma unroll
+    for (int e = 0; e < NPT; ++e) {
+      int pi = p0 + e;
+      pi = pi < npages ? pi : npages - 1;
+      phys[e] = __builtin_amdgcn_readfirstlane(bt[pi]);
+    }
+  }
+
+  // Issue the 2*NLT wave-loads of tile `tile`, whose page ids were looked up one step earlier (the table
+  // access is off the critical path of the loads).  `lane_off` is the lane id, or 0 in every lane for a
+  // placeholder issue whose data is never used (all lanes then fetch the same 16 bytes): issues stay
+  // unconditional, which keeps the order of outstanding loads known at compile time, so waiting for the
+  // oldest tile leaves the younger ones in flight.
+  static __device__ __forceinline__ void issue(uint4 (&kb)[NLT], uint4 (&vb)[NLT], int tile, const int (&phys)[NPT],
+                                               const T* k_pool, const T* v_pool, int log2_block, int lane_off) {
     const int tok0 = tile * TT;
 #pragma unroll
     for (int i = 0; i < NLT; ++i) {
       const int t = tok0 + i * TPL;
-      int pi = t >> log2_block;
-      pi = pi < npages ? pi : npages - 1;
-      const int phys = __builtin_amdgcn_readfirstlane(bt[pi]);
+      int ph = phys[0];
+#pragma unroll
+      for (int e = 1; e < NPT; ++e)
+        if (((i * TPL) >> log2_block) == e) ph = phys[e];
       const int slot0 = t & ((1 << log2_block) - 1);
-      const int64_t vec = (((int64_t)phys << log2_block) + slot0) * LPR + lane;
-      kb[i] = load_vec(k_pool, vec);
-      vb[i] = load_vec(v_pool, vec);
+      const int64_t vec = (((int64_t)ph << log2_block) + slot0) * LPR + lane_off;
+      kb[i] = load_vec_stream(k_pool, vec);
+      vb[i] = load_vec_stream(v_pool, vec);
     }
   }
 
-  static __device__ __forceinline__ void compute(uint4 (&kb)[NLT], uint4 (&vb)[NLT], int tile, int len, int grp,
+  // Consume NL wave-loads whose first token is tok0: logits, online softmax update, PV accumulation.
+  template <int NL>
+  static __device__ __forceinline__ void compute(uint4 (&kb)[NL], uint4 (&vb)[NL], int tok0, int len, int grp,
                                                  float scale_log2e, const QSlice<T> (&qs)[GP], float& m_run,
                                                  float& l_run, float (&acc)[G][EPL]) {
-    const int tok0 = tile * TT;
-    float x[NLT];
+    float x[NL];
 #pragma unroll
-    for (int i = 0; i < NLT; ++i) {
+    for (int i = 0; i < NL; ++i) {
       float sd[GP];
 #pragma unroll
       for (int j = 0; j < GP; ++j) sd[j] = qs[j].dot(kb[i]);
@@ -193,9 +224,9 @@ struct Tile {
       r = row_all_reduce<GP, LPR>(r);
       x[i] = r * scale_log2e;
     }
-    if (tok0 + TT > len) {  // the tile reaches past the row: mask logits, keep junk V out of the sum
+    if (tok0 + NL * TPL > len) {  // the tile reaches past the row: mask logits, keep junk V out of the sum
 #pragma unroll
-      for (int i = 0; i < NLT; ++i) {
+      for (int i = 0; i < NL; ++i) {
         const bool ok = tok0 + i * TPL + grp < len;
         x[i] = ok ? x[i] : kNegInf;
         if (!ok) vb[i] = make_uint4(0u, 0u, 0u, 0u);
@@ -203,13 +234,13 @@ struct Tile {
     }
     float m_new = m_run;
 #pragma unroll
-    for (int i = 0; i < NLT; ++i) m_new = fmaxf(m_new, x[i]);
+    for (int i = 0; i < NL; ++i) m_new = fmaxf(m_new, x[i]);
     const float m_safe = m_new == kNegInf ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-    float pr[NLT];
+    float pr[NL];
     float psum = 0.f;
 #pragma unroll
-    for (int i = 0; i < NLT; ++i) {
+    for (int i = 0; i < NL; ++i) {
       pr[i] = __builtin_amdgcn_exp2f(x[i] - m_safe);
       psum += pr[i];
     }
@@ -218,7 +249,7 @@ struct Tile {
     m_run = m_new;
     if (__builtin_amdgcn_ballot_w64(changed) != 0ull) rescale_acc<G, GP, EPL>(acc, alpha);
 #pragma unroll
-    for (int i = 0; i < NLT; ++i) {
+    for (int i = 0; i < NL; ++i) {
       float ve[EPL];
 #pragma unroll
       for (int e = 0; e < EPL; ++e) ve[e] = vec_elem<T>(vb[i], e);
@@ -227,12 +258,12 @@ struct Tile {
   }
 };
 
-template <typename T, int D, int G>
-__global__ __launch_bounds__(kThreads) void paged_decode_kernel(const DecodeParams p) {
+template <typename T, int D, int G, int WAVES, int DEPTH, bool FUSED>
+__global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const DecodeParams p) {
   using TL = Tile<T, D, G>;
   constexpr int EPL = TL::EPL, LPR = TL::LPR, TPL = TL::TPL, NLT = TL::NLT, TT = TL::TT, GP = TL::GP;
   constexpr int GBITS = ilog2(GP);
-  constexpr int NCONTRIB = kWaves * TPL;
+  constexpr int NCONTRIB = WAVES * TPL;
 
   __shared__ float sm_m[NCONTRIB][GP];
   __shared__ float sm_l[NCONTRIB][GP];
@@ -258,26 +289,42 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(const DecodePara
   }
   const int s = row / p.num_kv_heads;
   const int hk = row % p.num_kv_heads;
-  const int len = p.seq_lens[s];
-  const int npages = (len + (1 << p.log2_block) - 1) >> p.log2_block;
-  const int ntiles = (len + TT - 1) / TT;
-  const int t_begin = (int)(((int64_t)split * ntiles) / p.splits);
-  const int t_end = (int)(((int64_t)(split + 1) * ntiles) / p.splits);
   const int32_t* bt = p.block_table + (int64_t)row * p.max_blocks;
   const T* k_pool = static_cast<const T*>(p.k_pool);
   const T* v_pool = static_cast<const T*>(p.v_pool);
 
-  // query slices: slot i holds head (i ^ c_lane) of this KV head's group
+  // ---- prologue: everything that does not depend on the row length is requested first --------------
+  // query slices: slot i holds head (i ^ c_lane) of this KV head's group (heads past the group: zeros)
   QSlice<T> qs[GP];
 #pragma unroll
   for (int i = 0; i < GP; ++i) {
     const int head = i ^ c_lane;
-    if (head < p.g_real) {
-      qs[i].load(static_cast<const T*>(p.q) + ((int64_t)s * p.num_q_heads + hk * p.g_real + head) * D + u * EPL);
-    } else {
-      qs[i].zero();
-    }
+    const int head_ld = head < p.g_real ? head : 0;
+    qs[i].load(static_cast<const T*>(p.q) + ((int64_t)s * p.num_q_heads + hk * p.g_real + head_ld) * D + u * EPL);
   }
+  uint4 nk[1], nv[1];  // FUSED: the new token's K/V rows, held by the first lane group of every wave
+  if constexpr (FUSED) {
+    const int64_t vec = (int64_t)row * LPR + u;
+    nk[0] = load_vec(p.new_k, vec);
+    nv[0] = load_vec(p.new_v, vec);
+  }
+  const int len_pool = p.seq_lens[s];               // tokens that are read from the pool
+  const int len = FUSED ? len_pool + 1 : len_pool;  // tokens attended to
+#pragma unroll
+  for (int i = 0; i < GP; ++i)
+    if ((i ^ c_lane) >= p.g_real) qs[i].zero();
+  // FUSED: this workgroup has read the sequence length; the workgroup that arrives last (of the
+  // Hk * splits that share the sequence) may overwrite it at its end.
+  int arrived = 0;
+  if constexpr (FUSED) {
+    if (threadIdx.x == 0)
+      arrived = __hip_atomic_fetch_add(p.seq_counter + s, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  const int npages = (len_pool + (1 << p.log2_block) - 1) >> p.log2_block;
+  const int ntiles = (len_pool + TT - 1) / TT;
+  const int t_begin = (int)(((int64_t)split * ntiles) / p.splits);
+  const int t_end = (int)(((int64_t)(split + 1) * ntiles) / p.splits);
 
   float m_run = kNegInf;  // running max of head c_lane over this lane's stream of tokens
   float l_run = 0.f;
@@ -287,22 +334,72 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(const DecodePara
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
 
-  {
-    uint4 kb0[NLT], vb0[NLT], kb1[NLT], vb1[NLT];
-    int tile = t_begin + wave;
-    if (tile < t_end) TL::issue(kb0, vb0, tile, k_pool, v_pool, bt, npages, p.log2_block, lane);
-    while (tile < t_end) {
-      if (tile + kWaves < t_end) TL::issue(kb1, vb1, tile + kWaves, k_pool, v_pool, bt, npages, p.log2_block, lane);
-      TL::compute(kb0, vb0, tile, len, grp, p.scale_log2e, qs, m_run, l_run, acc);
-      tile += kWaves;
-      if (tile >= t_end) break;
-      if (tile + kWaves < t_end) TL::issue(kb0, vb0, tile + kWaves, k_pool, v_pool, bt, npages, p.log2_block, lane);
-      TL::compute(kb1, vb1, tile, len, grp, p.scale_log2e, qs, m_run, l_run, acc);
-      tile += kWaves;
+  // This wave's tiles are t_begin + wave + i*WAVES, i = 0 .. n_mine-1.  DEPTH register buffers: while
+  // tile i is consumed, tiles i+1 .. i+DEPTH-1 are in flight.
+  const int n_mine = (t_end - t_begin - wave + WAVES - 1) / WAVES;
+  if (n_mine > 0) {
+    uint4 kb[DEPTH][NLT], vb[DEPTH][NLT];
+    int phys[TL::NPT];  // page ids of the tile that is issued next
+    const int first = t_begin + wave;
+    const auto tile_at = [&](int i) { return first + (i < n_mine ? i : n_mine - 1) * WAVES; };
+    TL::lookup(phys, tile_at(0), bt, npages, p.log2_block);
+#pragma unroll
+    for (int d = 0; d < DEPTH - 1; ++d) {
+      TL::issue(kb[d], vb[d], tile_at(d), phys, k_pool, v_pool, p.log2_block, d < n_mine ? lane : 0);
+      TL::lookup(phys, tile_at(d + 1), bt, npages, p.log2_block);
+    }
+    for (int i = 0; i < n_mine; i += DEPTH) {
+#pragma unroll
+      for (int ph = 0; ph < DEPTH; ++ph) {
+        const int ahead = i + ph + DEPTH - 1;
+        TL::issue(kb[(ph + DEPTH - 1) % DEPTH], vb[(ph + DEPTH - 1) % DEPTH], tile_at(ahead), phys, k_pool, v_pool,
+                  p.log2_block, ahead < n_mine ? lane : 0);
+        TL::lookup(phys, tile_at(ahead + 1), bt, npages, p.log2_block);
+        if (i + ph < n_mine)
+          TL::template compute<NLT>(kb[ph], vb[ph], (first + (i + ph) * WAVES) * TT, len_pool, grp, p.scale_log2e, qs,
+                                    m_run, l_run, acc);
+      }
     }
   }
 
-  // ---- merge the kWaves x TPL token streams of this workgroup through LDS, one head at a time ----
+  if constexpr (FUSED) {
+    if (split == p.splits - 1) {
+      // the new token is token number len_pool of the row: wave 0 attends to it from registers ...
+      if (wave == 0)
+        TL::template compute<1>(nk, nv, len_pool, len_pool + (grp == 0 ? 1 : 0), 0, p.scale_log2e, qs, m_run, l_run,
+                                acc);
+      // ... and the first lane group of the last wave stores it into the pool, linking a new page first
+      // when the tail page is full (the page freed by the eviction just before, else the next spare)
+      if (wave == WAVES - 1) {
+        const int B = 1 << p.log2_block;
+        const int slot = len_pool & (B - 1);
+        const int jb = len_pool >> p.log2_block;
+        if (jb < p.max_blocks) {
+          int page;
+          if (slot == 0) {
+            page = p.freed_phys[row];
+            if (page < 0) {
+              const int used = p.spare_used[row];
+              page = used < p.n_spare ? p.spare[(int64_t)row * p.n_spare + used] : -1;
+              if (lane == 0) p.spare_used[row] = used + 1;
+            } else if (lane == 0) {
+              p.freed_phys[row] = -1;
+            }
+            if (lane == 0) const_cast<int32_t*>(bt)[jb] = page;
+          } else {
+            page = bt[jb];
+          }
+          if (page >= 0 && grp == 0) {
+            const int64_t vec = (((int64_t)page << p.log2_block) + slot) * LPR + u;
+            reinterpret_cast<uint4*>(const_cast<void*>(p.k_pool))[vec] = nk[0];
+            reinterpret_cast<uint4*>(const_cast<void*>(p.v_pool))[vec] = nv[0];
+          }
+        }
+      }
+    }
+  }
+
+  // ---- merge the WAVES x TPL token streams of this workgroup through LDS, one head at a time ----
   const int contrib = wave * TPL + grp;
   if (u < GP) {
     sm_m[contrib][c_lane] = m_run;
@@ -345,6 +442,12 @@ __global__ __launch_bounds__(kThreads) void paged_decode_kernel(const DecodePara
     }
     __syncthreads();
   }
+  if constexpr (FUSED) {
+    if (threadIdx.x == 0 && arrived == p.num_kv_heads * p.splits - 1) {
+      p.seq_counter[s] = 0;
+      const_cast<int32_t*>(p.seq_lens)[s] = len_pool + 1;
+    }
+  }
 }
 
 // Merge the split partials of one (sequence, query head): one workgroup of D threads.
@@ -378,7 +481,7 @@ __global__ __launch_bounds__(D) void paged_decode_reduce_kernel(const float* __r
   }
 }
 
-template <typename T, int D, int G>
+template <typename T, int D, int G, int WAVES, int DEPTH>
 hipError_t launch_one(const DecodeArgs& a, hipStream_t stream) {
   DecodeParams p;
   p.q = a.q;
@@ -395,11 +498,24 @@ hipError_t launch_one(const DecodeArgs& a, hipStream_t stream) {
   p.log2_block = ilog2(a.block_size);
   p.splits = a.splits;
   p.g_real = a.num_q_heads / a.num_kv_heads;
+  p.new_k = a.new_k;
+  p.new_v = a.new_v;
+  p.freed_phys = a.freed_phys;
+  p.spare = a.spare;
+  p.spare_used = a.spare_used;
+  p.seq_counter = a.seq_counter;
+  p.n_spare = a.n_spare;
   const int64_t rows = (int64_t)a.num_seqs * a.num_kv_heads;
   p.xcd_map = (a.xcd_map && rows % 8 == 0) ? 1 : 0;
   const int64_t grid = rows * a.splits;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((paged_decode_kernel<T, D, G>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+  if (a.new_k != nullptr) {
+    hipLaunchKernelGGL((paged_decode_kernel<T, D, G, WAVES, DEPTH, true>), dim3((unsigned)grid), dim3(WAVES * kWave), 0,
+                       stream, p);
+  } else {
+    hipLaunchKernelGGL((paged_decode_kernel<T, D, G, WAVES, DEPTH, false>), dim3((unsigned)grid), dim3(WAVES * kWave),
+                       0, stream, p);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.splits == 1) return e;
   hipLaunchKernelGGL((paged_decode_reduce_kernel<T, D>), dim3((unsigned)(a.num_seqs * a.num_q_heads)), dim3(D), 0,
@@ -407,20 +523,36 @@ hipError_t launch_one(const DecodeArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+template <typename T, int D, int G>
+hipError_t launch_variant(const DecodeArgs& a, hipStream_t stream) {
+  if constexpr (sizeof(T) == 2 && D == 128 && G == 4) {  // tuning variants for the headline shape
+    switch (a.waves * 10 + a.depth) {
+      case 42: return launch_one<T, D, G, 4, 2>(a, stream);
+      case 43: return launch_one<T, D, G, 4, 3>(a, stream);
+      case 82: return launch_one<T, D, G, 8, 2>(a, stream);
+      default: return hipErrorInvalidValue;
+    }
+  } else {
+    return launch_one<T, D, G, 4, 2>(a, stream);
+  }
+}
+
 template <typename T, int D>
 hipError_t launch_group(const DecodeArgs& a, hipStream_t stream) {
   const int g = a.num_q_heads / a.num_kv_heads;
   switch (g) {
-    case 1: return launch_one<T, D, 1>(a, stream);
-    case 2: return launch_one<T, D, 2>(a, stream);
-    case 3: return launch_one<T, D, 3>(a, stream);
-    case 4: return launch_one<T, D, 4>(a, stream);
-    case 5: case 6: case 7: case 8: return launch_one<T, D, 8>(a, stream);
+    case 1: return launch_variant<T, D, 1>(a, stream);
+    case 2: return launch_variant<T, D, 2>(a, stream);
+    case 3: return launch_variant<T, D, 3>(a, stream);
+    case 4: return launch_variant<T, D, 4>(a, stream);
+    case 5: case 6: case 7: case 8: return launch_variant<T, D, 8>(a, stream);
     default: return hipErrorInvalidValue;
   }
 }
 
 }  // namespace
+
+size_t decode_counter_bytes(int num_seqs) { return ((size_t)num_seqs * sizeof(int32_t) + 255) & ~(size_t)255; }
 
 size_t decode_partials_bytes(int num_seqs, int num_q_heads, int head_dim, int splits) {
   if (splits <= 1) return 0;

@@ -6,7 +6,8 @@
 
 namespace {
 
-int g_options[PE_OPT_COUNT_] = {0 /* decode splits: auto */, 1 /* XCD-aware workgroup order */};
+int g_options[PE_OPT_COUNT_] = {0 /* decode splits: auto */, 1 /* XCD-aware workgroup order */, 4 /* waves */,
+                                2 /* pipeline depth */};
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -67,6 +68,8 @@ int pe_set_option(int key, int value) {
   if (key < 0 || key >= PE_OPT_COUNT_) return PE_ERR_INVALID_ARG;
   if (key == PE_OPT_DECODE_SPLITS && (value < 0 || value > 256)) return PE_ERR_INVALID_ARG;
   if (key == PE_OPT_DECODE_XCD_MAP && value != 0 && value != 1) return PE_ERR_INVALID_ARG;
+  if (key == PE_OPT_DECODE_WAVES && value != 4 && value != 8 && value != 16) return PE_ERR_INVALID_ARG;
+  if (key == PE_OPT_DECODE_DEPTH && (value < 2 || value > 4)) return PE_ERR_INVALID_ARG;
   g_options[key] = value;
   return PE_OK;
 }
@@ -81,6 +84,9 @@ size_t pe_workspace_bytes(int op, const pe_cache_desc* desc, int64_t total_token
   switch (op) {
     case PE_OP_PAGED_DECODE:
       return pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, decode_splits(desc));
+    case PE_OP_APPEND_PAGED_DECODE:
+      return pe::decode_counter_bytes(desc->num_seqs) +
+             pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, decode_splits(desc));
     case PE_OP_PREFILL_PRUNE:
       if (total_tokens < 0) return 0;
       return pe::prune_workspace_bytes(desc->num_seqs, desc->num_kv_heads, total_tokens);
@@ -201,7 +207,58 @@ int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool
   a.max_blocks = desc->max_blocks;
   a.splits = splits;
   a.xcd_map = g_options[PE_OPT_DECODE_XCD_MAP];
+  a.waves = g_options[PE_OPT_DECODE_WAVES];
+  a.depth = g_options[PE_OPT_DECODE_DEPTH];
   a.is_bf16 = desc->dtype == PE_BF16;
+  return pe::launch_paged_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
+}
+
+int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const void* new_v, const void* q,
+                           void* k_pool, void* v_pool, int32_t* block_table, int32_t* seq_lens, int32_t* freed_phys,
+                           const int32_t* spare, int32_t* spare_used, int32_t n_spare, float softmax_scale, void* out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  const int st = check_desc(desc);
+  if (st != PE_OK) return st;
+  if (!new_k || !new_v || !q || !k_pool || !v_pool || !block_table || !seq_lens || !freed_phys || !spare ||
+      !spare_used || !out)
+    return PE_ERR_INVALID_ARG;
+  if (n_spare < 1) return PE_ERR_INVALID_ARG;
+  if (!aligned(k_pool, 16) || !aligned(v_pool, 16) || !aligned(q, 16) || !aligned(new_k, 16) || !aligned(new_v, 16))
+    return PE_ERR_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale) || softmax_scale - softmax_scale != 0.f) return PE_ERR_INVALID_ARG;
+  const int splits = decode_splits(desc);
+  const size_t counter_bytes = pe::decode_counter_bytes(desc->num_seqs);
+  const int ws = check_workspace(
+      workspace, workspace_bytes,
+      counter_bytes + pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, splits));
+  if (ws != PE_OK) return ws;
+  pe::DecodeArgs a;
+  a.q = q;
+  a.k_pool = k_pool;
+  a.v_pool = v_pool;
+  a.block_table = block_table;
+  a.seq_lens = seq_lens;
+  a.out = out;
+  a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes);
+  a.scale = softmax_scale;
+  a.num_seqs = desc->num_seqs;
+  a.num_kv_heads = desc->num_kv_heads;
+  a.num_q_heads = desc->num_q_heads;
+  a.head_dim = desc->head_dim;
+  a.block_size = desc->block_size;
+  a.max_blocks = desc->max_blocks;
+  a.splits = splits;
+  a.xcd_map = g_options[PE_OPT_DECODE_XCD_MAP];
+  a.waves = g_options[PE_OPT_DECODE_WAVES];
+  a.depth = g_options[PE_OPT_DECODE_DEPTH];
+  a.is_bf16 = desc->dtype == PE_BF16;
+  a.new_k = new_k;
+  a.new_v = new_v;
+  a.freed_phys = freed_phys;
+  a.spare = spare;
+  a.spare_used = spare_used;
+  a.seq_counter = static_cast<int32_t*>(workspace);
+  a.n_spare = n_spare;
   return pe::launch_paged_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
 

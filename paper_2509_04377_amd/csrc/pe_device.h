@@ -127,4 +127,12 @@ __device__ __forceinline__ uint4 load_vec(const void* base, int64_t vec_index) {
   return reinterpret_cast<const uint4*>(base)[vec_index];
 }
 
+// The same load with a non-temporal hint: K/V pages are read once per launch and should not displace
+// tables, queries and partials from the caches.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_vec_stream(const void* base, int64_t vec_index) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(base) + vec_index);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 }  // namespace pe

@@ -56,10 +56,20 @@ struct DecodeArgs {
   int num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, max_blocks;
   int splits;
   int xcd_map;
+  int waves, depth;  // workgroup size in waves, register pipeline depth
   bool is_bf16;
+  // fused append: all null / 0 for plain attention
+  const void* new_k = nullptr;
+  const void* new_v = nullptr;
+  int32_t* freed_phys = nullptr;
+  const int32_t* spare = nullptr;
+  int32_t* spare_used = nullptr;
+  int32_t* seq_counter = nullptr;
+  int n_spare = 0;
 };
 hipError_t launch_paged_decode(const DecodeArgs& a, hipStream_t stream);
 size_t decode_partials_bytes(int num_seqs, int num_q_heads, int head_dim, int splits);
+size_t decode_counter_bytes(int num_seqs);  // per-sequence arrival counters of the fused append
 
 struct PruneArgs {
   const void* k_in;

@@ -33,8 +33,11 @@ class LayeredCache:
             self.per_layer.append(c)
         # one split workspace serves every layer: launches are ordered on one stream
         self.decode_ws = pe.alloc_workspace(pe.PE_OP_PAGED_DECODE, self.per_layer[0].desc, device=device)
+        self.fused_ws = pe.alloc_zeroed_workspace(pe.PE_OP_APPEND_PAGED_DECODE, self.per_layer[0].desc, device=device)
         for c in self.per_layer:
             c.decode_ws = self.decode_ws
+            c.fused_ws = self.fused_ws
+        self.fused = True
         self.host_lens = [0] * num_seqs   # the same in every layer
 
     def prefill_prune_layer(self, layer, k_in, v_in, cu_seqlens, max_seqlen, kept_idx_out=None, workspace=None):
@@ -55,10 +58,15 @@ class LayeredCache:
             self.folded.evict_blocks()
             self.host_lens = [n - self.B if t else n for n, t in zip(self.host_lens, trig)]
         for l, c in enumerate(self.per_layer):
-            c.append_kv(new_k[l], new_v[l])
-            if layer_hook is not None:
-                layer_hook(l, 0)
-            c.paged_decode(q[l], out[l], softmax_scale)
+            if self.fused:
+                if layer_hook is not None:
+                    layer_hook(l, 0)
+                c.append_paged_decode(new_k[l], new_v[l], q[l], out[l], softmax_scale)
+            else:
+                c.append_kv(new_k[l], new_v[l])
+                if layer_hook is not None:
+                    layer_hook(l, 0)
+                c.paged_decode(q[l], out[l], softmax_scale)
             if layer_hook is not None:
                 layer_hook(l, 1)
         self.host_lens = [n + 1 for n in self.host_lens]

@@ -286,3 +286,55 @@ def test_append_kv_matches_oracle():
         assert np.array_equal(fd.cpu().numpy(), o["f"]) and np.array_equal(ud.cpu().numpy(), o["u"])
         assert np.array_equal(f32(kd).view(np.int32), o["k"].view(np.int32))
         assert np.array_equal(f32(vd).view(np.int32), o["v"].view(np.int32))
+
+
+@pytest.mark.parametrize("dt,D,B,G", [("bf16", 128, 16, 4), ("bf16", 64, 16, 4), ("f32", 64, 16, 2), ("bf16", 128, 32, 3),
+                                      ("f32", 128, 32, 1), ("bf16", 64, 32, 8)])
+def test_append_paged_decode_fused(dt, D, B, G):
+    """The one-launch append + attention against the oracle's append followed by its attention, three
+    steps in a row: tables, lengths, spare/freed bookkeeping and pool contents bit-exact, output in
+    tolerance.  Rows at a page boundary take a freed page or a spare one; one sequence is empty."""
+    print("case append_paged_decode_fused", dt, D, B, G, flush=True)
+    Hk = 2
+    lens = [0, 1, B - 1, B, 2 * B, 5 * B + 3, 40 * B, 40 * B - 1, 1300]
+    k_pool, v_pool, table, sl = make_paged(800 + D + B + G, lens, Hk, D, B, DTYPES[dt], extra=2, pad_pages=64)
+    S, Hq, mb, P = len(lens), Hk * G, table.shape[2], k_pool.shape[0]
+    used = set(int(x) for x in table.flatten() if x >= 0)
+    free = [p for p in range(P) if p not in used]
+    n_spare = 2
+    spare = torch.tensor(free[:S * Hk * n_spare], dtype=torch.int32).reshape(S, Hk, n_spare)
+    freed = torch.full((S, Hk), -1, dtype=torch.int32)
+    freed[3, 0] = free[-1]            # sequence 3 (len == B) re-uses a "freed" page in head 0, a spare in head 1
+    freed[6, 1] = free[-2]
+    spare_used = torch.zeros((S, Hk), dtype=torch.int32)
+    o = dict(k=f32(k_pool), v=f32(v_pool), t=i32(table).copy(), l=i32(sl).copy(), f=i32(freed).copy(),
+             u=i32(spare_used).copy())
+    desc = pe.make_desc(DTYPES[dt], S, Hk, Hq, D, B, mb, P)
+    kd, vd, td, ld, fd, sd, ud = (x.to(DEV) for x in (k_pool, v_pool, table, sl, freed, spare, spare_used))
+    g = torch.Generator().manual_seed(801)
+    try:
+        for step, splits in enumerate((1, 3, 0)):
+            pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, splits)
+            ws = pe.alloc_zeroed_workspace(pe.PE_OP_APPEND_PAGED_DECODE, desc)
+            nk = torch.randn((S, Hk, D), generator=g).to(DTYPES[dt])
+            nv = torch.randn((S, Hk, D), generator=g).to(DTYPES[dt])
+            q = torch.randn((S, Hq, D), generator=g).to(DTYPES[dt])
+            oracle.append_kv(f32(nk), f32(nv), o["k"], o["v"], o["t"], o["l"], o["f"], i32(spare), o["u"])
+            want = oracle.paged_decode(f32(q), o["k"], o["v"], o["t"], o["l"])
+            out = torch.full((S, Hq, D), 7.0, dtype=DTYPES[dt], device=DEV)
+            for rep in range(2 if step == 2 else 1):    # the workspace counters must come back to zero
+                if rep == 1:                             # second launch of the same step on restored state
+                    td.copy_(t_before); ld.copy_(l_before); fd.copy_(f_before); ud.copy_(u_before)
+                t_before, l_before, f_before, u_before = td.clone(), ld.clone(), fd.clone(), ud.clone()
+                pe.pe_append_paged_decode(desc, nk.to(DEV), nv.to(DEV), q.to(DEV), kd, vd, td, ld, fd, sd, ud,
+                                          D ** -0.5, out, ws)
+                torch.cuda.synchronize()
+                assert int(ws[:4 * S].view(torch.int32).abs().sum()) == 0, "arrival counters not reset"
+                assert np.array_equal(td.cpu().numpy(), o["t"]) and np.array_equal(ld.cpu().numpy(), o["l"])
+                assert np.array_equal(fd.cpu().numpy(), o["f"]) and np.array_equal(ud.cpu().numpy(), o["u"])
+                assert np.array_equal(f32(kd).view(np.int32), o["k"].view(np.int32))
+                assert np.array_equal(f32(vd).view(np.int32), o["v"].view(np.int32))
+                e2, emax = rel_err(f32(out), want)
+                assert e2 <= TOL[dt] and emax <= TOL[dt], (step, rep, e2, emax)
+    finally:
+        pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, 0)
