@@ -162,19 +162,20 @@ int pe_append_kv(const pe_cache_desc* desc, const void* new_k, const void* new_v
                  int32_t* spare_used, int32_t n_spare, void* stream);
 
 /*
- * The two calls above in ONE launch: exactly the effect of pe_append_kv followed by pe_paged_decode
- * (Alg. 3: the new token joins the cache, then "PagedAttention(Q,K,V)" over everything cached), i.e.
- * attention over the seq_lens[s] cached tokens plus the new token, the new K/V rows stored into the
- * tail page (a new page linked in first when seq_lens[s] % B == 0), seq_lens[s] += 1.  The new rows
- * are attended to from registers instead of being read back from the pool.
- * workspace: pe_workspace_bytes(PE_OP_APPEND_PAGED_DECODE, desc, 0).  Its leading
- * ((4*S + 255) & ~255) bytes hold per-sequence arrival counters: they must be ZERO before the first
- * call that uses this workspace (e.g. hipMemsetAsync once) and every call leaves them zero.
+ * The two calls above in ONE launch: the effect of pe_append_kv followed by pe_paged_decode (Alg. 3: the
+ * new token joins the cache, then "PagedAttention(Q,K,V)" over everything cached), i.e. attention over
+ * the seq_lens[s] cached tokens plus the new token, the new K/V rows stored into the tail page (a new
+ * page linked in first when seq_lens[s] % B == 0).  The new rows are attended to from registers instead
+ * of being read back from the pool.  seq_lens is only read; the new lengths seq_lens[s] + 1 are written
+ * to seq_lens_out [S], which must not alias seq_lens (callers keep two arrays and swap them), so that no
+ * workgroup of the launch can observe a length that another one has already bumped.
+ * workspace: pe_workspace_bytes(PE_OP_APPEND_PAGED_DECODE, desc, 0).
  */
 int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const void* new_v, const void* q,
-                           void* k_pool, void* v_pool, int32_t* block_table, int32_t* seq_lens, int32_t* freed_phys,
-                           const int32_t* spare, int32_t* spare_used, int32_t n_spare, float softmax_scale, void* out,
-                           void* workspace, size_t workspace_bytes, void* stream);
+                           void* k_pool, void* v_pool, int32_t* block_table, const int32_t* seq_lens,
+                           int32_t* seq_lens_out, int32_t* freed_phys, const int32_t* spare, int32_t* spare_used,
+                           int32_t n_spare, float softmax_scale, void* out, void* workspace, size_t workspace_bytes,
+                           void* stream);
 
 #ifdef __cplusplus
 }

@@ -72,7 +72,8 @@ def lib():
         L.pe_append_kv.restype = ctypes.c_int
         L.pe_append_kv.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.pe_append_paged_decode.restype = ctypes.c_int
-        L.pe_append_paged_decode.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ctypes.c_float, vp, vp, sz, vp]
+        L.pe_append_paged_decode.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ctypes.c_float, vp, vp, sz,
+                                             vp]
         _lib = L
     return _lib
 
@@ -181,23 +182,18 @@ def pe_append_kv(desc, new_k, new_v, k_pool, v_pool, block_table, seq_lens, free
                               int(spare.shape[-1]), _stream()), "pe_append_kv")
 
 
-def pe_append_paged_decode(desc, new_k, new_v, q, k_pool, v_pool, block_table, seq_lens, freed_phys, spare, spare_used,
-                           softmax_scale, out, workspace):
+def pe_append_paged_decode(desc, new_k, new_v, q, k_pool, v_pool, block_table, seq_lens, seq_lens_out, freed_phys, spare,
+                           spare_used, softmax_scale, out, workspace=None):
     wp, wn = _ws(workspace)
     _check(lib().pe_append_paged_decode(ctypes.byref(desc), _ptr(new_k, "new_k"), _ptr(new_v, "new_v"), _ptr(q, "q"),
                                         _ptr(k_pool, "k_pool"), _ptr(v_pool, "v_pool"),
                                         _ptr(block_table, "block_table", torch.int32),
                                         _ptr(seq_lens, "seq_lens", torch.int32),
+                                        _ptr(seq_lens_out, "seq_lens_out", torch.int32),
                                         _ptr(freed_phys, "freed_phys", torch.int32), _ptr(spare, "spare", torch.int32),
                                         _ptr(spare_used, "spare_used", torch.int32), int(spare.shape[-1]),
                                         ctypes.c_float(softmax_scale), _ptr(out, "out"), wp, wn, _stream()),
            "pe_append_paged_decode")
-
-
-def alloc_zeroed_workspace(op: int, desc: pe_cache_desc, device="cuda"):
-    """Workspace for calls that keep arrival counters in it: zero-filled once, left zero by every call."""
-    n = pe_workspace_bytes(op, desc, 0)
-    return torch.zeros((n + 255) // 256 * 256, dtype=torch.uint8, device=device)
 
 
 @dataclass
@@ -218,7 +214,7 @@ class PagedCache:
     budget: int
     decode_ws: torch.Tensor = None
     host_lens: list = None     # host mirror of seq_lens (pure integer bookkeeping, never read back)
-    fused_ws: torch.Tensor = None  # workspace of pe_append_paged_decode (arrival counters + split partials)
+    seq_lens_alt: torch.Tensor = None  # second lengths array for pe_append_paged_decode (swapped after each call)
 
     @staticmethod
     def create(dtype, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, layout, budget, device="cuda",
@@ -258,10 +254,12 @@ class PagedCache:
     def append_paged_decode(self, new_k, new_v, q, out, softmax_scale=None):
         if softmax_scale is None:
             softmax_scale = float(self.desc.head_dim) ** -0.5
-        if self.fused_ws is None:
-            self.fused_ws = alloc_zeroed_workspace(PE_OP_APPEND_PAGED_DECODE, self.desc, device=q.device)
+        if self.seq_lens_alt is None:
+            self.seq_lens_alt = torch.empty_like(self.seq_lens)
         pe_append_paged_decode(self.desc, new_k, new_v, q, self.k_pool, self.v_pool, self.block_table, self.seq_lens,
-                               self.freed_phys, self.spare, self.spare_used, softmax_scale, out, self.fused_ws)
+                               self.seq_lens_alt, self.freed_phys, self.spare, self.spare_used, softmax_scale, out,
+                               self.decode_ws)
+        self.seq_lens, self.seq_lens_alt = self.seq_lens_alt, self.seq_lens
 
     def decode_step(self, new_k, new_v, q, out, softmax_scale=None, fused=True):
         """One decode iteration of one layer (Alg. 3): score + evict when some sequence's newest page has

@@ -20,7 +20,8 @@
 // The FUSED variant also performs the harness append of the same decode iteration: the new token's K/V
 // rows are taken from registers as one extra token of the row (they are not read back from the pool),
 // the last split's workgroup links a new page if the tail page is full and stores the rows into the
-// pool, and the workgroup that arrives last at a per-sequence counter bumps seq_lens.
+// pool, and the new lengths go to a second array (the caller swaps the two), so no workgroup can see a
+// length that another one has already bumped.
 #include "pe_device.h"
 #include "pe_launch.h"
 
@@ -156,7 +157,7 @@ struct DecodeParams {
   int32_t* freed_phys;
   const int32_t* spare;
   int32_t* spare_used;
-  int32_t* seq_counter;  // [S], zero between launches
+  int32_t* seq_lens_out;  // [S], must not alias seq_lens
   int n_spare;
 };
 
@@ -313,14 +314,15 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
 #pragma unroll
   for (int i = 0; i < GP; ++i)
     if ((i ^ c_lane) >= p.g_real) qs[i].zero();
-  // FUSED: this workgroup has read the sequence length; the workgroup that arrives last (of the
-  // Hk * splits that share the sequence) may overwrite it at its end.
-  int arrived = 0;
+  // FUSED: requests for what the append needs, issued now and used after the main loop
+  const bool appender = FUSED && split == p.splits - 1 && wave == WAVES - 1;  // wave-uniform
+  int ap_freed = -1, ap_used = 0;
   if constexpr (FUSED) {
-    if (threadIdx.x == 0)
-      arrived = __hip_atomic_fetch_add(p.seq_counter + s, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (appender) {
+      ap_freed = p.freed_phys[row];
+      ap_used = p.spare_used[row];
+    }
   }
-
   const int npages = (len_pool + (1 << p.log2_block) - 1) >> p.log2_block;
   const int ntiles = (len_pool + TT - 1) / TT;
   const int t_begin = (int)(((int64_t)split * ntiles) / p.splits);
@@ -363,39 +365,37 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
   }
 
   if constexpr (FUSED) {
-    if (split == p.splits - 1) {
-      // the new token is token number len_pool of the row: wave 0 attends to it from registers ...
-      if (wave == 0)
-        TL::template compute<1>(nk, nv, len_pool, len_pool + (grp == 0 ? 1 : 0), 0, p.scale_log2e, qs, m_run, l_run,
-                                acc);
-      // ... and the first lane group of the last wave stores it into the pool, linking a new page first
-      // when the tail page is full (the page freed by the eviction just before, else the next spare)
-      if (wave == WAVES - 1) {
-        const int B = 1 << p.log2_block;
-        const int slot = len_pool & (B - 1);
-        const int jb = len_pool >> p.log2_block;
-        if (jb < p.max_blocks) {
-          int page;
-          if (slot == 0) {
-            page = p.freed_phys[row];
-            if (page < 0) {
-              const int used = p.spare_used[row];
-              page = used < p.n_spare ? p.spare[(int64_t)row * p.n_spare + used] : -1;
-              if (lane == 0) p.spare_used[row] = used + 1;
-            } else if (lane == 0) {
-              p.freed_phys[row] = -1;
-            }
-            if (lane == 0) const_cast<int32_t*>(bt)[jb] = page;
-          } else {
-            page = bt[jb];
+    // the new token is token number len_pool of the row: wave 0 of the last split attends to it from
+    // registers ...
+    if (split == p.splits - 1 && wave == 0)
+      TL::template compute<1>(nk, nv, len_pool, len_pool + (grp == 0 ? 1 : 0), 0, p.scale_log2e, qs, m_run, l_run, acc);
+    // ... and the first lane group of its last wave stores it into the pool, linking a new page first when
+    // the tail page is full (the page freed by the eviction just before, else the next spare)
+    if (appender) {
+      const int B = 1 << p.log2_block;
+      const int slot = len_pool & (B - 1);
+      const int jb = len_pool >> p.log2_block;
+      if (jb < p.max_blocks) {
+        int page;
+        if (slot == 0) {
+          page = ap_freed;
+          if (page < 0) {
+            page = ap_used < p.n_spare ? p.spare[(int64_t)row * p.n_spare + ap_used] : -1;
+            if (lane == 0) p.spare_used[row] = ap_used + 1;
+          } else if (lane == 0) {
+            p.freed_phys[row] = -1;
           }
-          if (page >= 0 && grp == 0) {
-            const int64_t vec = (((int64_t)page << p.log2_block) + slot) * LPR + u;
-            reinterpret_cast<uint4*>(const_cast<void*>(p.k_pool))[vec] = nk[0];
-            reinterpret_cast<uint4*>(const_cast<void*>(p.v_pool))[vec] = nv[0];
-          }
+          if (lane == 0) const_cast<int32_t*>(bt)[jb] = page;
+        } else {
+          page = bt[jb];
+        }
+        if (page >= 0 && grp == 0) {
+          const int64_t vec = (((int64_t)page << p.log2_block) + slot) * LPR + u;
+          reinterpret_cast<uint4*>(const_cast<void*>(p.k_pool))[vec] = nk[0];
+          reinterpret_cast<uint4*>(const_cast<void*>(p.v_pool))[vec] = nv[0];
         }
       }
+      if (hk == 0 && lane == 0) p.seq_lens_out[s] = len_pool + 1;
     }
   }
 
@@ -441,12 +441,6 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
       }
     }
     __syncthreads();
-  }
-  if constexpr (FUSED) {
-    if (threadIdx.x == 0 && arrived == p.num_kv_heads * p.splits - 1) {
-      p.seq_counter[s] = 0;
-      const_cast<int32_t*>(p.seq_lens)[s] = len_pool + 1;
-    }
   }
 }
 
@@ -503,7 +497,7 @@ hipError_t launch_one(const DecodeArgs& a, hipStream_t stream) {
   p.freed_phys = a.freed_phys;
   p.spare = a.spare;
   p.spare_used = a.spare_used;
-  p.seq_counter = a.seq_counter;
+  p.seq_lens_out = a.seq_lens_out;
   p.n_spare = a.n_spare;
   const int64_t rows = (int64_t)a.num_seqs * a.num_kv_heads;
   p.xcd_map = (a.xcd_map && rows % 8 == 0) ? 1 : 0;
@@ -551,8 +545,6 @@ hipError_t launch_group(const DecodeArgs& a, hipStream_t stream) {
 }
 
 }  // namespace
-
-size_t decode_counter_bytes(int num_seqs) { return ((size_t)num_seqs * sizeof(int32_t) + 255) & ~(size_t)255; }
 
 size_t decode_partials_bytes(int num_seqs, int num_q_heads, int head_dim, int splits) {
   if (splits <= 1) return 0;

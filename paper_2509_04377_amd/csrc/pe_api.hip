@@ -85,8 +85,7 @@ size_t pe_workspace_bytes(int op, const pe_cache_desc* desc, int64_t total_token
     case PE_OP_PAGED_DECODE:
       return pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, decode_splits(desc));
     case PE_OP_APPEND_PAGED_DECODE:
-      return pe::decode_counter_bytes(desc->num_seqs) +
-             pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, decode_splits(desc));
+      return pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, decode_splits(desc));
     case PE_OP_PREFILL_PRUNE:
       if (total_tokens < 0) return 0;
       return pe::prune_workspace_bytes(desc->num_seqs, desc->num_kv_heads, total_tokens);
@@ -214,23 +213,24 @@ int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool
 }
 
 int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const void* new_v, const void* q,
-                           void* k_pool, void* v_pool, int32_t* block_table, int32_t* seq_lens, int32_t* freed_phys,
-                           const int32_t* spare, int32_t* spare_used, int32_t n_spare, float softmax_scale, void* out,
-                           void* workspace, size_t workspace_bytes, void* stream) {
+                           void* k_pool, void* v_pool, int32_t* block_table, const int32_t* seq_lens,
+                           int32_t* seq_lens_out, int32_t* freed_phys, const int32_t* spare, int32_t* spare_used,
+                           int32_t n_spare, float softmax_scale, void* out, void* workspace, size_t workspace_bytes,
+                           void* stream) {
   const int st = check_desc(desc);
   if (st != PE_OK) return st;
-  if (!new_k || !new_v || !q || !k_pool || !v_pool || !block_table || !seq_lens || !freed_phys || !spare ||
-      !spare_used || !out)
+  if (!new_k || !new_v || !q || !k_pool || !v_pool || !block_table || !seq_lens || !seq_lens_out || !freed_phys ||
+      !spare || !spare_used || !out)
     return PE_ERR_INVALID_ARG;
+  if (seq_lens_out == seq_lens) return PE_ERR_INVALID_ARG;
   if (n_spare < 1) return PE_ERR_INVALID_ARG;
   if (!aligned(k_pool, 16) || !aligned(v_pool, 16) || !aligned(q, 16) || !aligned(new_k, 16) || !aligned(new_v, 16))
     return PE_ERR_INVALID_ARG;
   if (!(softmax_scale == softmax_scale) || softmax_scale - softmax_scale != 0.f) return PE_ERR_INVALID_ARG;
   const int splits = decode_splits(desc);
-  const size_t counter_bytes = pe::decode_counter_bytes(desc->num_seqs);
   const int ws = check_workspace(
       workspace, workspace_bytes,
-      counter_bytes + pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, splits));
+      pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, splits));
   if (ws != PE_OK) return ws;
   pe::DecodeArgs a;
   a.q = q;
@@ -239,7 +239,7 @@ int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const v
   a.block_table = block_table;
   a.seq_lens = seq_lens;
   a.out = out;
-  a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes);
+  a.partials = static_cast<float*>(workspace);
   a.scale = softmax_scale;
   a.num_seqs = desc->num_seqs;
   a.num_kv_heads = desc->num_kv_heads;
@@ -257,7 +257,7 @@ int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const v
   a.freed_phys = freed_phys;
   a.spare = spare;
   a.spare_used = spare_used;
-  a.seq_counter = static_cast<int32_t*>(workspace);
+  a.seq_lens_out = seq_lens_out;
   a.n_spare = n_spare;
   return pe::launch_paged_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }

@@ -64,12 +64,11 @@ struct DecodeArgs {
   int32_t* freed_phys = nullptr;
   const int32_t* spare = nullptr;
   int32_t* spare_used = nullptr;
-  int32_t* seq_counter = nullptr;
+  int32_t* seq_lens_out = nullptr;
   int n_spare = 0;
 };
 hipError_t launch_paged_decode(const DecodeArgs& a, hipStream_t stream);
 size_t decode_partials_bytes(int num_seqs, int num_q_heads, int head_dim, int splits);
-size_t decode_counter_bytes(int num_seqs);  // per-sequence arrival counters of the fused append
 
 struct PruneArgs {
   const void* k_in;

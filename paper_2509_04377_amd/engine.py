@@ -33,10 +33,11 @@ class LayeredCache:
             self.per_layer.append(c)
         # one split workspace serves every layer: launches are ordered on one stream
         self.decode_ws = pe.alloc_workspace(pe.PE_OP_PAGED_DECODE, self.per_layer[0].desc, device=device)
-        self.fused_ws = pe.alloc_zeroed_workspace(pe.PE_OP_APPEND_PAGED_DECODE, self.per_layer[0].desc, device=device)
-        for c in self.per_layer:
+        # second lengths array for the fused append + attention call; all layers swap in lockstep
+        f.seq_lens_alt = torch.empty_like(f.seq_lens)
+        for l, c in enumerate(self.per_layer):
             c.decode_ws = self.decode_ws
-            c.fused_ws = self.fused_ws
+            c.seq_lens_alt = f.seq_lens_alt[l * num_seqs:(l + 1) * num_seqs]
         self.fused = True
         self.host_lens = [0] * num_seqs   # the same in every layer
 
@@ -69,5 +70,7 @@ class LayeredCache:
                 c.paged_decode(q[l], out[l], softmax_scale)
             if layer_hook is not None:
                 layer_hook(l, 1)
+        if self.fused:   # every layer wrote its new lengths into the other array
+            self.folded.seq_lens, self.folded.seq_lens_alt = self.folded.seq_lens_alt, self.folded.seq_lens
         self.host_lens = [n + 1 for n in self.host_lens]
         return any(trig)

