@@ -173,19 +173,29 @@ def main():
     torch.cuda.synchronize()
 
     # ---- timed region: exactly --steps steps ---------------------------------------------------------
-    samples = []          # (event_start, event_end, algorithmic bytes) per sampled attention launch
+    # (event_start, event_end, launches between them, algorithmic bytes of those launches).  With the fused
+    # append the attention launches of a step run back to back, so one event pair brackets all of them and
+    # the event overhead is not charged to each launch; unfused, every attention launch gets its own pair.
+    samples = []
     state = {}
 
     def hook(layer, phase):
-        if phase == 0:
-            e = torch.cuda.Event(enable_timing=True)
-            e.record()
-            state["e0"] = e
+        per_launch = (sum(eng.host_lens) + S) * Hk * D * 2 * elem   # host_lens is bumped after the layer loop
+        if eng.fused:
+            if layer == 0 and phase == 0:
+                state["e0"] = torch.cuda.Event(enable_timing=True)
+                state["e0"].record()
+            elif layer == L - 1 and phase == 1:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                samples.append((state["e0"], e, L, per_launch * L))
+        elif phase == 0:
+            state["e0"] = torch.cuda.Event(enable_timing=True)
+            state["e0"].record()
         else:
             e = torch.cuda.Event(enable_timing=True)
             e.record()
-            cached = sum(eng.host_lens) + S          # host_lens is bumped after the layer loop
-            samples.append((state["e0"], e, cached * Hk * D * 2 * elem))
+            samples.append((state["e0"], e, 1, per_launch))
 
     step_events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     n_trigger = 0
@@ -219,19 +229,18 @@ def main():
                           "sweep_GBps": prune_bytes / (sorted(prune_ms)[len(prune_ms) // 2] * 1e-3) / 1e9},
     }
     if samples:
-        durs = [a.elapsed_time(b) * 1e-3 for a, b, _ in samples]
-        avg_dur = sum(durs) / len(durs)
-        avg_bytes = sum(nb for _, _, nb in samples) / len(samples)
+        n_launch = sum(n for _, _, n, _ in samples)
+        avg_dur = sum(a.elapsed_time(b) * 1e-3 for a, b, _, _ in samples) / n_launch
+        avg_bytes = sum(nb for _, _, _, nb in samples) / n_launch
         achieved = avg_bytes / avg_dur / 1e9
         result["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(wl.name),
-                              "kernel": "paged_decode_kernel", "launches_timed": len(samples),
+                              "kernel": "paged_decode_kernel", "launches_timed": n_launch,
                               "avg_launch_us": avg_dur * 1e6, "algorithmic_bytes_per_launch": avg_bytes}
     # whole-step algorithmic bytes: attention every step + the score sweep on trigger steps
-    att_bytes = L * Hk * D * 2 * elem * (sum(eng.host_lens) - S * args.steps / 2.0)   # rough mean over the run
     result["path_GBps"] = None
     if samples:
-        mean_cached = sum(nb for _, _, nb in samples) / len(samples)        # per layer
+        mean_cached = avg_bytes                                              # per layer launch
         score_bytes = L * S * Hk * (wl.budget // wl.block_size) * wl.block_size * D * 2 * elem
         total_bytes = mean_cached * L * args.steps + score_bytes * n_trigger
         result["path_GBps"] = total_bytes / elapsed / 1e9

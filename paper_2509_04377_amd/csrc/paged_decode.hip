@@ -175,16 +175,19 @@ struct Tile {
   // A tile touches at most NPT pages (two when a 32-token tile meets 16-token pages).
   static constexpr int NPT = TT > 16 ? TT / 16 : 1;
 
-  // Scalar loads of the physical page ids of tile `tile`.  Entries beyond the row's last page are
-  // redirected to the last page (their tokens are masked later), so every address stays inside the pool.
-  static __device__ __forceinline__ void lookup(int (&phys)[NPT], int tile, const int32_t* bt, int npages,
+  // Scalar loads of the physical page ids of tile `tile`.  The index is clamped to the table row, and an
+  // unused entry (-1, beyond the row's last page) is replaced by page 0: the tokens of such a page are
+  // masked later, so any address inside the pool will do.  Nothing here depends on the row length, so
+  // the first lookup can be issued before the length has arrived.
+  static __device__ __forceinline__ void lookup(int (&phys)[NPT], int tile, const int32_t* bt, int max_blocks,
                                                 int log2_block) {
     const int p0 = (tile * TT) >> log2_block;
 #pragma unroll
     for (int e = 0; e < NPT; ++e) {
       int pi = p0 + e;
-      pi = pi < npages ? pi : npages - 1;
-      phys[e] = __builtin_amdgcn_readfirstlane(bt[pi]);
+      pi = pi < max_blocks ? pi : max_blocks - 1;
+      const int ph = __builtin_amdgcn_readfirstlane(bt[pi]);
+      phys[e] = ph < 0 ? 0 : ph;
     }
   }
 
@@ -266,9 +269,10 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
   constexpr int GBITS = ilog2(GP);
   constexpr int NCONTRIB = WAVES * TPL;
 
+  constexpr int HC = G < 4 ? G : 4;  // heads merged per LDS pass
   __shared__ float sm_m[NCONTRIB][GP];
   __shared__ float sm_l[NCONTRIB][GP];
-  __shared__ __attribute__((aligned(16))) float sm_acc[NCONTRIB][D];
+  __shared__ __attribute__((aligned(16))) float sm_acc[NCONTRIB][HC][D];
 
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
@@ -309,6 +313,10 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
     nk[0] = load_vec(p.new_k, vec);
     nv[0] = load_vec(p.new_v, vec);
   }
+  // page ids of the tile that is issued next; with one split the wave's first tile is tile `wave`
+  // whatever the row length, so its lookup travels together with the length itself
+  int phys[TL::NPT];
+  if (p.splits == 1) TL::lookup(phys, wave, bt, p.max_blocks, p.log2_block);
   const int len_pool = p.seq_lens[s];               // tokens that are read from the pool
   const int len = FUSED ? len_pool + 1 : len_pool;  // tokens attended to
 #pragma unroll
@@ -323,7 +331,6 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
       ap_used = p.spare_used[row];
     }
   }
-  const int npages = (len_pool + (1 << p.log2_block) - 1) >> p.log2_block;
   const int ntiles = (len_pool + TT - 1) / TT;
   const int t_begin = (int)(((int64_t)split * ntiles) / p.splits);
   const int t_end = (int)(((int64_t)(split + 1) * ntiles) / p.splits);
@@ -341,14 +348,13 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
   const int n_mine = (t_end - t_begin - wave + WAVES - 1) / WAVES;
   if (n_mine > 0) {
     uint4 kb[DEPTH][NLT], vb[DEPTH][NLT];
-    int phys[TL::NPT];  // page ids of the tile that is issued next
     const int first = t_begin + wave;
     const auto tile_at = [&](int i) { return first + (i < n_mine ? i : n_mine - 1) * WAVES; };
-    TL::lookup(phys, tile_at(0), bt, npages, p.log2_block);
+    if (p.splits != 1) TL::lookup(phys, first, bt, p.max_blocks, p.log2_block);
 #pragma unroll
     for (int d = 0; d < DEPTH - 1; ++d) {
       TL::issue(kb[d], vb[d], tile_at(d), phys, k_pool, v_pool, p.log2_block, d < n_mine ? lane : 0);
-      TL::lookup(phys, tile_at(d + 1), bt, npages, p.log2_block);
+      TL::lookup(phys, tile_at(d + 1), bt, p.max_blocks, p.log2_block);
     }
     for (int i = 0; i < n_mine; i += DEPTH) {
 #pragma unroll
@@ -356,7 +362,7 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
         const int ahead = i + ph + DEPTH - 1;
         TL::issue(kb[(ph + DEPTH - 1) % DEPTH], vb[(ph + DEPTH - 1) % DEPTH], tile_at(ahead), phys, k_pool, v_pool,
                   p.log2_block, ahead < n_mine ? lane : 0);
-        TL::lookup(phys, tile_at(ahead + 1), bt, npages, p.log2_block);
+        TL::lookup(phys, tile_at(ahead + 1), bt, p.max_blocks, p.log2_block);
         if (i + ph < n_mine)
           TL::template compute<NLT>(kb[ph], vb[ph], (first + (i + ph) * WAVES) * TT, len_pool, grp, p.scale_log2e, qs,
                                     m_run, l_run, acc);
@@ -399,7 +405,7 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
     }
   }
 
-  // ---- merge the WAVES x TPL token streams of this workgroup through LDS, one head at a time ----
+  // ---- merge the WAVES x TPL token streams of this workgroup through LDS, up to four heads per pass ----
   const int contrib = wave * TPL + grp;
   if (u < GP) {
     sm_m[contrib][c_lane] = m_run;
@@ -407,22 +413,35 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
   }
   __syncthreads();
 #pragma unroll
-  for (int h = 0; h < G; ++h) {
-    float mm = kNegInf;
-    for (int c = 0; c < NCONTRIB; ++c) mm = fmaxf(mm, sm_m[c][h]);
-    const float ms = mm == kNegInf ? 0.f : mm;
-    const float f = __builtin_amdgcn_exp2f(sm_m[contrib][h] - ms);
-    float4* dst = reinterpret_cast<float4*>(&sm_acc[contrib][u * EPL]);
+  for (int h0 = 0; h0 < G; h0 += HC) {
+    if (h0 > 0) __syncthreads();  // the previous pass has been read
 #pragma unroll
-    for (int e = 0; e < EPL; e += 4)
-      dst[e / 4] = make_float4(acc[h][e] * f, acc[h][e + 1] * f, acc[h][e + 2] * f, acc[h][e + 3] * f);
+    for (int hh = 0; hh < HC; ++hh) {
+      const int h = h0 + hh;
+      if (h < G) {
+        float mm = kNegInf;
+        for (int c = 0; c < NCONTRIB; ++c) mm = fmaxf(mm, sm_m[c][h]);
+        const float ms = mm == kNegInf ? 0.f : mm;
+        const float f = __builtin_amdgcn_exp2f(sm_m[contrib][h] - ms);
+        float4* dst = reinterpret_cast<float4*>(&sm_acc[contrib][hh][u * EPL]);
+#pragma unroll
+        for (int e = 0; e < EPL; e += 4)
+          dst[e / 4] = make_float4(acc[h][e] * f, acc[h][e + 1] * f, acc[h][e + 2] * f, acc[h][e + 3] * f);
+      }
+    }
     __syncthreads();
-    const int d = (int)threadIdx.x;
-    if (d < D && h < p.g_real) {
-      float ll = 0.f;
-      for (int c = 0; c < NCONTRIB; ++c) ll = fmaf(sm_l[c][h], __builtin_amdgcn_exp2f(sm_m[c][h] - ms), ll);
-      float o = 0.f;
-      for (int c = 0; c < NCONTRIB; ++c) o += sm_acc[c][d];
+    for (int idx = (int)threadIdx.x; idx < HC * D; idx += WAVES * kWave) {
+      const int hh = idx / D, d = idx % D;
+      const int h = h0 + hh;
+      if (h >= p.g_real) continue;
+      float mm = kNegInf;
+      for (int c = 0; c < NCONTRIB; ++c) mm = fmaxf(mm, sm_m[c][h]);
+      const float ms = mm == kNegInf ? 0.f : mm;
+      float ll = 0.f, o = 0.f;
+      for (int c = 0; c < NCONTRIB; ++c) {
+        ll = fmaf(sm_l[c][h], __builtin_amdgcn_exp2f(sm_m[c][h] - ms), ll);
+        o += sm_acc[c][hh][d];
+      }
       if (p.splits == 1) {
         const float r = ll > 0.f ? o / ll : 0.f;
         const int64_t off = ((int64_t)s * p.num_q_heads + hk * p.g_real + h) * D + d;
@@ -440,7 +459,6 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
         }
       }
     }
-    __syncthreads();
   }
 }
 

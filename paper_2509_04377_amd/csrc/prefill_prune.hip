@@ -79,8 +79,8 @@ __global__ __launch_bounds__(kThreads) void token_scores_kernel(const T* __restr
       const int64_t r = base_row + i * TPL + grp;
       if (r < total_rows) {
         const int64_t vec = (base_row + i * TPL) * LPR + lane;
-        kb[buf][i] = load_vec(k_in, vec);
-        vb[buf][i] = load_vec(v_in, vec);
+        kb[buf][i] = load_vec_stream(k_in, vec);
+        vb[buf][i] = load_vec_stream(v_in, vec);
       } else {
         kb[buf][i] = make_uint4(0u, 0u, 0u, 0u);
         vb[buf][i] = make_uint4(0u, 0u, 0u, 0u);

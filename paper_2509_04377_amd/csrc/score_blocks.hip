@@ -46,8 +46,8 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
       const int64_t base = (int64_t)bt[j] * kVecPerPage + lane;
 #pragma unroll
       for (int i = 0; i < NL; ++i) {
-        kb[buf][i] = load_vec(k_pool, base + i * kWave);
-        vb[buf][i] = load_vec(v_pool, base + i * kWave);
+        kb[buf][i] = load_vec_stream(k_pool, base + i * kWave);
+        vb[buf][i] = load_vec_stream(v_pool, base + i * kWave);
       }
     }
   };
