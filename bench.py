@@ -37,9 +37,9 @@ def parse_args():
     ap.add_argument("--sample-every", type=int, default=8, help="time the attention launches of every n-th step")
     ap.add_argument("--unfused", action="store_true", help="separate append and attention launches per layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seqs", type=int, default=8)
+    ap.add_argument("--cpu-seqs", type=int, default=16)
     ap.add_argument("--cpu-layers", type=int, default=2)
-    ap.add_argument("--cpu-steps", type=int, default=17)
+    ap.add_argument("--cpu-steps", type=int, default=33)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference dispatch for rocprofv3 --pmc scaling)")
     return ap.parse_args()
@@ -123,8 +123,8 @@ def cpu_baseline(wl, seed, n_seqs, n_layers, steps):
     tokens_per_s = S / (per_layer_step * wl.layers)
     return {"value": tokens_per_s, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": "%d of %d sequences x %d of %d layers x %d consecutive decode steps from the pruned state "
-                      "(evictions at steps 1 and 17), %.1f s wall; scaled to all layers"
-                      % (S, wl.num_seqs, n_layers, wl.layers, steps, dt),
+                      "(an eviction every %d steps, the first at step 1), %.1f s wall; scaled to all layers"
+                      % (S, wl.num_seqs, n_layers, wl.layers, steps, wl.block_size, dt),
             "ms_per_layer_step": per_layer_step * 1e3}
 
 

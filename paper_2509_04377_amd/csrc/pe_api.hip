@@ -26,15 +26,17 @@ int check_desc(const pe_cache_desc* d) {
   return PE_OK;
 }
 
-// Number of splits of a row in pe_paged_decode: enough workgroups to give each of the 256 CUs
-// about four, but no split shorter than a handful of tiles.
+// Number of splits of a row in pe_paged_decode.  The kernel streams best with ONE four-wave workgroup per
+// compute unit (each wave keeps a tile in flight while it consumes another; more resident workgroups only
+// add prologue, epilogue and merge work), so rows are split just enough to cover the 256 compute units of
+// an MI355X, and never into splits shorter than 256 tokens.
 int decode_splits(const pe_cache_desc* d) {
   if (g_options[PE_OPT_DECODE_SPLITS] > 0) return g_options[PE_OPT_DECODE_SPLITS];
   const int64_t rows = (int64_t)d->num_seqs * d->num_kv_heads;
-  const int64_t target_groups = 1024;
-  int64_t splits = (target_groups + rows - 1) / rows;
+  const int64_t compute_units = 256;
+  int64_t splits = (compute_units + rows - 1) / rows;
   const int64_t max_tokens = (int64_t)d->max_blocks * d->block_size;
-  const int64_t max_by_len = max_tokens / 128 > 1 ? max_tokens / 128 : 1;
+  const int64_t max_by_len = max_tokens / 256 > 1 ? max_tokens / 256 : 1;
   if (splits > max_by_len) splits = max_by_len;
   if (splits > 64) splits = 64;
   if (splits < 1) splits = 1;
