@@ -363,9 +363,10 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
         TL::issue(kb[(ph + DEPTH - 1) % DEPTH], vb[(ph + DEPTH - 1) % DEPTH], tile_at(ahead), phys, k_pool, v_pool,
                   p.log2_block, ahead < n_mine ? lane : 0);
         TL::lookup(phys, tile_at(ahead + 1), bt, p.max_blocks, p.log2_block);
-        if (i + ph < n_mine)
+        if (i + ph < n_mine) {
           TL::template compute<NLT>(kb[ph], vb[ph], (first + (i + ph) * WAVES) * TT, len_pool, grp, p.scale_log2e, qs,
                                     m_run, l_run, acc);
+        }
       }
     }
   }
