@@ -138,6 +138,24 @@ int pe_evict_blocks(const pe_cache_desc* desc, const float* scores, int32_t* blo
                     int32_t budget_tokens, int32_t* evicted_logical_out, int32_t* freed_phys_out, void* stream);
 
 /*
+ * Cached page scores (an optimisation of (1)+(3), not the paper's stated procedure, which re-scores every
+ * page on every trigger; Sec. 3 "computed on-the-fly"): a full page's tokens never change, so neither
+ * does its score.  A caller may keep scores[S][Hk][max_blocks] alive across steps:
+ *   - pe_score_recent_blocks computes only the `recent` >= 1 most recently filled pages of every row,
+ *     j in [max(0, seq_lens[s]/B - recent), seq_lens[s]/B), and leaves every other entry untouched;
+ *   - pe_evict_blocks_cached is pe_evict_blocks that also deletes entry j* from the score row (later
+ *     scores shift left with the table, the vacated tail entry becomes +INF).
+ * Starting from a pe_score_blocks call (which also sets the +INF entries), the array then always equals
+ * what pe_score_blocks would return, and the decisions are the same.
+ */
+int pe_score_recent_blocks(const pe_cache_desc* desc, const void* k_pool, const void* v_pool,
+                           const int32_t* block_table, const int32_t* seq_lens, int32_t recent,
+                           float* scores_inout, void* stream);
+int pe_evict_blocks_cached(const pe_cache_desc* desc, float* scores_inout, int32_t* block_table, int32_t* seq_lens,
+                           int32_t budget_tokens, int32_t* evicted_logical_out, int32_t* freed_phys_out,
+                           void* stream);
+
+/*
  * (4) Paged decode attention -- Eq. 1 for one new query per sequence; Alg. 3 "PagedAttention(Q,K,V)".
  *     out[s][h][:] = sum_t softmax_t(softmax_scale * <q[s][h], K_t>) V_t over the seq_lens[s] tokens of
  *     row (s, h / (Hq/Hk)), token t being slot t % B of page block_table[s][hk][t / B].

@@ -23,7 +23,7 @@ PE_OPT_DECODE_SPLITS, PE_OPT_DECODE_XCD_MAP, PE_OPT_DECODE_WAVES, PE_OPT_DECODE_
 
 EXPORTS = ["pe_workspace_bytes", "pe_status_string", "pe_version", "pe_set_option", "pe_get_option",
            "pe_score_blocks", "pe_prefill_prune", "pe_evict_blocks", "pe_paged_decode", "pe_append_kv",
-           "pe_append_paged_decode"]
+           "pe_append_paged_decode", "pe_score_recent_blocks", "pe_evict_blocks_cached"]
 
 
 class pe_cache_desc(ctypes.Structure):
@@ -74,6 +74,10 @@ def lib():
         L.pe_append_paged_decode.restype = ctypes.c_int
         L.pe_append_paged_decode.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ctypes.c_float, vp, vp, sz,
                                              vp]
+        L.pe_score_recent_blocks.restype = ctypes.c_int
+        L.pe_score_recent_blocks.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp]
+        L.pe_evict_blocks_cached.restype = ctypes.c_int
+        L.pe_evict_blocks_cached.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -167,6 +171,24 @@ def pe_evict_blocks(desc, scores, block_table, seq_lens, budget_tokens, evicted_
                                  _ptr(freed_phys_out, "freed_phys_out", torch.int32), _stream()), "pe_evict_blocks")
 
 
+def pe_score_recent_blocks(desc, k_pool, v_pool, block_table, seq_lens, recent, scores_inout):
+    _check(lib().pe_score_recent_blocks(ctypes.byref(desc), _ptr(k_pool, "k_pool"), _ptr(v_pool, "v_pool"),
+                                        _ptr(block_table, "block_table", torch.int32),
+                                        _ptr(seq_lens, "seq_lens", torch.int32), int(recent),
+                                        _ptr(scores_inout, "scores_inout", torch.float32), _stream()),
+           "pe_score_recent_blocks")
+
+
+def pe_evict_blocks_cached(desc, scores_inout, block_table, seq_lens, budget_tokens, evicted_logical_out,
+                           freed_phys_out):
+    _check(lib().pe_evict_blocks_cached(ctypes.byref(desc), _ptr(scores_inout, "scores_inout", torch.float32),
+                                        _ptr(block_table, "block_table", torch.int32),
+                                        _ptr(seq_lens, "seq_lens", torch.int32), int(budget_tokens),
+                                        _ptr(evicted_logical_out, "evicted_logical_out", torch.int32),
+                                        _ptr(freed_phys_out, "freed_phys_out", torch.int32), _stream()),
+           "pe_evict_blocks_cached")
+
+
 def pe_paged_decode(desc, q, k_pool, v_pool, block_table, seq_lens, softmax_scale, out, workspace=None):
     wp, wn = _ws(workspace)
     _check(lib().pe_paged_decode(ctypes.byref(desc), _ptr(q, "q"), _ptr(k_pool, "k_pool"), _ptr(v_pool, "v_pool"),
@@ -215,6 +237,8 @@ class PagedCache:
     decode_ws: torch.Tensor = None
     host_lens: list = None     # host mirror of seq_lens (pure integer bookkeeping, never read back)
     seq_lens_alt: torch.Tensor = None  # second lengths array for pe_append_paged_decode (swapped after each call)
+    cached_scores: bool = False    # keep `scores` alive across steps and score only newly filled pages
+    host_scored: list = None       # per sequence: full pages whose score is in `scores` (host bookkeeping)
 
     @staticmethod
     def create(dtype, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, layout, budget, device="cuda",
@@ -267,8 +291,7 @@ class PagedCache:
         alone, so the host decides it without reading anything back."""
         B = self.desc.block_size
         if self.any_trigger():
-            self.score_blocks()
-            self.evict_blocks()
+            self.score_and_evict()
             self.host_lens = [n - B if (n > 0 and n % B == 0 and n >= self.budget) else n for n in self.host_lens]
         if fused:
             self.append_paged_decode(new_k, new_v, q, out, softmax_scale)
@@ -283,6 +306,27 @@ class PagedCache:
     def evict_blocks(self):
         pe_evict_blocks(self.desc, self.scores, self.block_table, self.seq_lens, self.budget, self.evicted_logical,
                         self.freed_phys)
+
+    def score_and_evict(self):
+        """Score + evict of a trigger step.  With cached scores only the pages filled since the last call are
+        scored (all of them the first time) and the eviction keeps the score rows aligned with the table."""
+        B = self.desc.block_size
+        if not self.cached_scores:
+            self.score_blocks()
+            self.evict_blocks()
+            return
+        full = [n // B for n in self.host_lens]
+        if self.host_scored is None:
+            self.score_blocks()
+        else:
+            recent = max(f - sc for f, sc in zip(full, self.host_scored))
+            if recent > 0:
+                pe_score_recent_blocks(self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, recent,
+                                       self.scores)
+        pe_evict_blocks_cached(self.desc, self.scores, self.block_table, self.seq_lens, self.budget,
+                               self.evicted_logical, self.freed_phys)
+        self.host_scored = [f - 1 if (n > 0 and n % B == 0 and n >= self.budget) else f
+                            for f, n in zip(full, self.host_lens)]
 
     def append_kv(self, new_k, new_v):
         pe_append_kv(self.desc, new_k, new_v, self.k_pool, self.v_pool, self.block_table, self.seq_lens,

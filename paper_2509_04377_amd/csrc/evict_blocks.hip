@@ -1,6 +1,9 @@
 // Decode-time eviction (Alg. 3: "Evict One page with the lowest score", "Update the KV Cache Block
 // Table") and the harness append step that follows it in a decode iteration.
 //
+// With a caller-kept score array (scores are immutable per full page) the evicted entry is deleted from
+// the score row too, so that scores stay aligned with the table.
+//
 // evict: one workgroup per sequence, one wave per (sequence, KV head) row at a time.  The wave finds
 // argmin_j (score_j, j) over the row's full pages with a lane-strided scan and a lexicographic
 // wave reduction (ties: lowest logical index), then shifts the table entries behind the evicted one
@@ -25,7 +28,7 @@ __device__ __forceinline__ void min_step(float& sc, int& idx) {
   }
 }
 
-__global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* __restrict__ scores,
+__global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* scores, float* scores_mut,
                                                                 int32_t* __restrict__ block_table,
                                                                 int32_t* __restrict__ seq_lens,
                                                                 int32_t* __restrict__ evicted_logical,
@@ -70,14 +73,22 @@ __global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* __r
     __builtin_amdgcn_s_waitcnt(0);  // the evicted entry has been read before any store below is issued
     // stable left shift of entries jstar+1 .. n-1; each pass loads its 64 sources before it stores,
     // and a pass only stores to positions that later passes do not read.
+    float* sc_mut = scores_mut != nullptr ? scores_mut + row * max_blocks : nullptr;
     for (int base = (jstar / kWave) * kWave; base < n; base += kWave) {
       const int j = base + lane;
       const bool move = j >= jstar && j < n;
       int32_t v = -1;
-      if (move && j + 1 < n) v = bt[j + 1];
+      float sv = __builtin_inff();
+      if (move && j + 1 < n) {
+        v = bt[j + 1];
+        if (sc_mut != nullptr) sv = sc_mut[j + 1];
+      }
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       __builtin_amdgcn_s_waitcnt(0);  // all 64 sources are in registers before the stores are issued
-      if (move) bt[j] = v;
+      if (move) {
+        bt[j] = v;
+        if (sc_mut != nullptr) sc_mut[j] = sv;
+      }
     }
     if (lane == 0) {
       evicted_logical[row] = jstar;
@@ -137,7 +148,7 @@ __global__ __launch_bounds__(kThreads) void append_kv_kernel(const uint4* __rest
 
 hipError_t launch_evict_blocks(const EvictArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL(evict_blocks_kernel, dim3((unsigned)a.num_seqs), dim3(kThreads), 0, stream, a.scores,
-                     a.block_table, a.seq_lens, a.evicted_logical, a.freed_phys, a.num_kv_heads, a.block_size,
+                     a.scores_mut, a.block_table, a.seq_lens, a.evicted_logical, a.freed_phys, a.num_kv_heads, a.block_size,
                      a.max_blocks, a.budget);
   return hipGetLastError();
 }

@@ -96,11 +96,29 @@ size_t pe_workspace_bytes(int op, const pe_cache_desc* desc, int64_t total_token
   }
 }
 
+namespace {
+int score_blocks_impl(const pe_cache_desc* desc, const void* k_pool, const void* v_pool, const int32_t* block_table,
+                      const int32_t* seq_lens, float* scores_out, int recent, void* stream);
+}
+
 int pe_score_blocks(const pe_cache_desc* desc, const void* k_pool, const void* v_pool, const int32_t* block_table,
                     const int32_t* seq_lens, float* scores_out, void* workspace, size_t workspace_bytes,
                     void* stream) {
   (void)workspace;
   (void)workspace_bytes;
+  return score_blocks_impl(desc, k_pool, v_pool, block_table, seq_lens, scores_out, 0, stream);
+}
+
+int pe_score_recent_blocks(const pe_cache_desc* desc, const void* k_pool, const void* v_pool,
+                           const int32_t* block_table, const int32_t* seq_lens, int32_t recent,
+                           float* scores_inout, void* stream) {
+  if (recent < 1) return PE_ERR_INVALID_ARG;
+  return score_blocks_impl(desc, k_pool, v_pool, block_table, seq_lens, scores_inout, recent, stream);
+}
+
+namespace {
+int score_blocks_impl(const pe_cache_desc* desc, const void* k_pool, const void* v_pool, const int32_t* block_table,
+                      const int32_t* seq_lens, float* scores_out, int recent, void* stream) {
   const int st = check_desc(desc);
   if (st != PE_OK) return st;
   if (!k_pool || !v_pool || !block_table || !seq_lens || !scores_out) return PE_ERR_INVALID_ARG;
@@ -117,8 +135,10 @@ int pe_score_blocks(const pe_cache_desc* desc, const void* k_pool, const void* v
   a.block_size = desc->block_size;
   a.max_blocks = desc->max_blocks;
   a.is_bf16 = desc->dtype == PE_BF16;
+  a.recent = recent;
   return pe::launch_score_blocks(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
+}  // namespace
 
 int pe_prefill_prune(const pe_cache_desc* desc, const void* k_in, const void* v_in, const int32_t* cu_seqlens,
                      int64_t total_tokens, int32_t max_seqlen, int32_t budget_tokens, void* k_pool, void* v_pool,
@@ -158,14 +178,36 @@ int pe_prefill_prune(const pe_cache_desc* desc, const void* k_in, const void* v_
   return pe::launch_prefill_prune(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
 
+namespace {
+int evict_blocks_impl(const pe_cache_desc* desc, const float* scores, float* scores_mut, int32_t* block_table,
+                      int32_t* seq_lens, int32_t budget_tokens, int32_t* evicted_logical_out, int32_t* freed_phys_out,
+                      void* stream);
+}
+
 int pe_evict_blocks(const pe_cache_desc* desc, const float* scores, int32_t* block_table, int32_t* seq_lens,
                     int32_t budget_tokens, int32_t* evicted_logical_out, int32_t* freed_phys_out, void* stream) {
+  return evict_blocks_impl(desc, scores, nullptr, block_table, seq_lens, budget_tokens, evicted_logical_out,
+                           freed_phys_out, stream);
+}
+
+int pe_evict_blocks_cached(const pe_cache_desc* desc, float* scores_inout, int32_t* block_table, int32_t* seq_lens,
+                           int32_t budget_tokens, int32_t* evicted_logical_out, int32_t* freed_phys_out,
+                           void* stream) {
+  return evict_blocks_impl(desc, scores_inout, scores_inout, block_table, seq_lens, budget_tokens,
+                           evicted_logical_out, freed_phys_out, stream);
+}
+
+namespace {
+int evict_blocks_impl(const pe_cache_desc* desc, const float* scores, float* scores_mut, int32_t* block_table,
+                      int32_t* seq_lens, int32_t budget_tokens, int32_t* evicted_logical_out, int32_t* freed_phys_out,
+                      void* stream) {
   const int st = check_desc(desc);
   if (st != PE_OK) return st;
   if (!scores || !block_table || !seq_lens || !evicted_logical_out || !freed_phys_out) return PE_ERR_INVALID_ARG;
   if (budget_tokens <= 0 || budget_tokens % desc->block_size != 0) return PE_ERR_INVALID_ARG;
   pe::EvictArgs a;
   a.scores = scores;
+  a.scores_mut = scores_mut;
   a.block_table = block_table;
   a.seq_lens = seq_lens;
   a.evicted_logical = evicted_logical_out;
@@ -177,6 +219,7 @@ int pe_evict_blocks(const pe_cache_desc* desc, const float* scores, int32_t* blo
   a.budget = budget_tokens;
   return pe::launch_evict_blocks(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
+}  // namespace
 
 int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool, const void* v_pool,
                     const int32_t* block_table, const int32_t* seq_lens, float softmax_scale, void* out,

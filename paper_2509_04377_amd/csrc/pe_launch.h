@@ -16,11 +16,13 @@ struct ScoreArgs {
   float* scores;
   int num_seqs, num_kv_heads, head_dim, block_size, max_blocks;
   bool is_bf16;
+  int recent = 0;  // 0: score every page; n > 0: only the n most recently filled pages of each row
 };
 hipError_t launch_score_blocks(const ScoreArgs& a, hipStream_t stream);
 
 struct EvictArgs {
   const float* scores;
+  float* scores_mut = nullptr;  // when set (== scores): delete the evicted entry from the score row as well
   int32_t* block_table;
   int32_t* seq_lens;
   int32_t* evicted_logical;

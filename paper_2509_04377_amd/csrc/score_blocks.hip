@@ -3,6 +3,10 @@
 // One wave sweeps one page: every lane loads 16 bytes, consecutive lanes consecutive addresses, so a
 // wave-load covers 1 KiB of the page.  Sums of squares are accumulated in fp64, reduced over the
 // lanes of a token row, and the page mean is summed in slot order and rounded once to fp32.
+//
+// A page's score never changes once the page is full (its tokens are immutable), so a caller that
+// keeps the score array alive may ask for the most recently filled pages only (`recent` > 0): the
+// kernel then visits pages nfull - recent .. nfull - 1 of every row and leaves the other entries alone.
 #include "pe_device.h"
 #include "pe_launch.h"
 #include "pe_norms.h"
@@ -21,7 +25,7 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
                                                                 const int32_t* __restrict__ block_table,
                                                                 const int32_t* __restrict__ seq_lens,
                                                                 float* __restrict__ scores, int num_kv_heads,
-                                                                int max_blocks, int groups_per_row) {
+                                                                int max_blocks, int groups_per_row, int recent) {
   using G = RowGeom<T, D>;
   constexpr int LPR = G::kLanesPerRow;
   constexpr int TPL = G::kTokensPerLoad;
@@ -38,7 +42,10 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
   const int nfull = seq_lens[s] / B;
   const int32_t* bt = block_table + (int64_t)row * max_blocks;
   float* out = scores + (int64_t)row * max_blocks;
-  const int j0 = grp * kPagesPerGroup + wave;
+  // recent == 0: every entry of the row; else only the last `recent` full pages
+  const int j_first = recent > 0 ? (nfull > recent ? nfull - recent : 0) : 0;
+  const int j_end = recent > 0 ? nfull : max_blocks;
+  const int j0 = j_first + grp * kPagesPerGroup + wave;
 
   uint4 kb[2][NL], vb[2][NL];
   auto issue = [&](int buf, int j) {
@@ -57,7 +64,7 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
   for (int it = 0; it < kPagesPerWave; ++it) {
     const int j = j0 + it * kWaves;
     if (it + 1 < kPagesPerWave) issue((it + 1) & 1, j + kWaves);
-    if (j >= max_blocks) break;
+    if (j >= j_end) break;
     if (j >= nfull) {
       if (lane == 0) out[j] = __builtin_inff();
       continue;
@@ -84,19 +91,18 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
     }
     if (lane == 0) out[j] = (float)(sum / (double)B);
   }
-  // entries of this group that no wave visited (max_blocks not a multiple of the group) do not exist:
-  // the loop above covers j0 + it*kWaves for all it, i.e. every j of the group below max_blocks.
 }
 
 template <typename T, int D, int B>
 hipError_t launch(const ScoreArgs& a, hipStream_t stream) {
-  const int groups_per_row = (a.max_blocks + kPagesPerGroup - 1) / kPagesPerGroup;
+  const int span = a.recent > 0 ? (a.recent < a.max_blocks ? a.recent : a.max_blocks) : a.max_blocks;
+  const int groups_per_row = (span + kPagesPerGroup - 1) / kPagesPerGroup;
   const int64_t rows = (int64_t)a.num_seqs * a.num_kv_heads;
   const int64_t grid = rows * groups_per_row;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL((score_blocks_kernel<T, D, B>), dim3((unsigned)grid), dim3(kThreads), 0, stream,
                      (const T*)a.k_pool, (const T*)a.v_pool, a.block_table, a.seq_lens, a.scores,
-                     a.num_kv_heads, a.max_blocks, groups_per_row);
+                     a.num_kv_heads, a.max_blocks, groups_per_row, a.recent);
   return hipGetLastError();
 }
 

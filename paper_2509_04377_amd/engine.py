@@ -55,8 +55,8 @@ class LayeredCache:
         """new_k, new_v [layers, S, Hk, D]; q, out [layers, S, Hq, D].  One decode iteration of all layers."""
         trig = self._triggers()
         if any(trig):
-            self.folded.score_blocks()
-            self.folded.evict_blocks()
+            self.folded.host_lens = self.host_lens * self.layers
+            self.folded.score_and_evict()
             self.host_lens = [n - self.B if t else n for n, t in zip(self.host_lens, trig)]
         for l, c in enumerate(self.per_layer):
             if self.fused:

@@ -30,7 +30,7 @@ def _compare_state(cache_gpu, cache_cpu, where):
     assert np.array_equal(cache_gpu.spare_used.cpu().numpy(), cache_cpu.spare_used), where
 
 
-def run_loop(wl, steps, layer=0, check_pool=True, fused=True):
+def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=False):
     """One layer of workload `wl`: prune, then `steps` decode steps on both sides, compared every step."""
     lens = synth.context_lengths(wl, SEED)
     k_in, v_in, cu = synth.prompt_kv(wl, layer, lens, SEED)
@@ -42,6 +42,7 @@ def run_loop(wl, steps, layer=0, check_pool=True, fused=True):
     kept = torch.full((S, Hk, wl.budget), -9, dtype=torch.int32, device=DEV)
     gcache.prefill_prune(k_in.to(DEV), v_in.to(DEV), cu.to(DEV), max(lens), kept)
     gcache.set_host_lens(lens)
+    gcache.cached_scores = cached_scores
     torch.cuda.synchronize()
     assert np.array_equal(kept.cpu().numpy(), okept)
     _compare_state(gcache, ocache, "after prune")
@@ -65,6 +66,15 @@ def run_loop(wl, steps, layer=0, check_pool=True, fused=True):
         if triggered:
             n_evictions += 1
             gs = gcache.scores.cpu().numpy()
+            if cached_scores:   # the kept array has already lost the evicted entry of every row that evicted
+                want_sc = oscores.copy()
+                for s_ in range(S):
+                    for h_ in range(Hk):
+                        j = oev[s_, h_]
+                        if j >= 0:
+                            want_sc[s_, h_, j:-1] = oscores[s_, h_, j + 1:]
+                            want_sc[s_, h_, -1] = np.inf
+                oscores = want_sc
             assert np.array_equal(np.isinf(gs), np.isinf(oscores)), where
             fin = np.isfinite(oscores)
             assert _ulp(gs[fin], oscores[fin]).max() <= 1, where
@@ -95,6 +105,16 @@ def test_tiny_under_budget_growth():
     wl = synth.TINY.with_(context=(40,), budget=64)
     n_ev, _ = run_loop(wl, 60)
     assert n_ev == 3
+
+
+@pytest.mark.parametrize("wl,steps,n_want", [(synth.TINY, 70, 5), (synth.TINY.with_(context=(40,), budget=64), 60, 3),
+                                             (synth.LLAMA32_1B.with_(budget=512), 36, 3)])
+def test_cached_scores_give_the_same_decisions(wl, steps, n_want):
+    """Scores kept across steps (only newly filled pages scored, score rows compacted with the table) must
+    equal the oracle's full re-scoring at every trigger, and so must every decision."""
+    print("case loop cached scores", wl.name, flush=True)
+    n_ev, _ = run_loop(wl, steps, cached_scores=True)
+    assert n_ev == n_want
 
 
 def test_tiny_full_cache_never_evicts():
