@@ -34,6 +34,7 @@ def parse_args():
     ap.add_argument("--xcd-map", type=int, default=None, choices=(0, 1))
     ap.add_argument("--waves", type=int, default=None)
     ap.add_argument("--depth", type=int, default=None)
+    ap.add_argument("--loads", type=int, default=None)
     ap.add_argument("--sample-every", type=int, default=8, help="time the attention launches of every n-th step")
     ap.add_argument("--unfused", action="store_true", help="separate append and attention launches per layer")
     ap.add_argument("--cached-scores", action="store_true",
@@ -154,6 +155,8 @@ def main():
         pe.pe_set_option(pe.PE_OPT_DECODE_WAVES, args.waves)
     if args.depth is not None:
         pe.pe_set_option(pe.PE_OPT_DECODE_DEPTH, args.depth)
+    if args.loads is not None:
+        pe.pe_set_option(pe.PE_OPT_DECODE_LOADS, args.loads)
 
     eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev)
     eng.fused = not args.unfused

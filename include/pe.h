@@ -81,11 +81,15 @@ const char* pe_status_string(int status);
 /* ABI version: major*10000 + minor*100 + patch. */
 int pe_version(void);
 
-/* Tuning knobs (host side, process wide, not thread safe).  key PE_OPT_DECODE_SPLITS: number of
- * splits of a row in pe_paged_decode (0 = choose from the shape).  Returns PE_OK or
- * PE_ERR_INVALID_ARG.  pe_workspace_bytes() follows the current setting. */
+/* Tuning knobs (host side, process wide, not thread safe).  PE_OPT_DECODE_SPLITS: number of splits of a
+ * row in pe_paged_decode (0 = choose from the shape); pe_workspace_bytes() follows the current setting.
+ * PE_OPT_DECODE_XCD_MAP: 1 = workgroup order that keeps the splits of a row on one XCD.
+ * PE_OPT_DECODE_WAVES / _DEPTH / _LOADS: waves per workgroup (4, 8), register buffers (2, 3) and wave-loads
+ * per tile (2, 4) of the decode kernel; only the bf16, head_dim 128, group 4 instantiation honours values
+ * other than the defaults 4 / 2 / 2 (an unsupported combination makes the decode call return PE_ERR_HIP).
+ * Returns PE_OK or PE_ERR_INVALID_ARG. */
 enum { PE_OPT_DECODE_SPLITS = 0, PE_OPT_DECODE_XCD_MAP = 1, PE_OPT_DECODE_WAVES = 2, PE_OPT_DECODE_DEPTH = 3,
-       PE_OPT_COUNT_ = 4 };
+       PE_OPT_DECODE_LOADS = 4, PE_OPT_COUNT_ = 5 };
 int pe_set_option(int key, int value);
 int pe_get_option(int key);
 

@@ -20,6 +20,7 @@ PE_F32, PE_BF16 = 0, 1
 PE_OP_SCORE_BLOCKS, PE_OP_PREFILL_PRUNE, PE_OP_EVICT_BLOCKS, PE_OP_PAGED_DECODE = 0, 1, 2, 3
 PE_OP_APPEND_PAGED_DECODE = 4
 PE_OPT_DECODE_SPLITS, PE_OPT_DECODE_XCD_MAP, PE_OPT_DECODE_WAVES, PE_OPT_DECODE_DEPTH = 0, 1, 2, 3
+PE_OPT_DECODE_LOADS = 4
 
 EXPORTS = ["pe_workspace_bytes", "pe_status_string", "pe_version", "pe_set_option", "pe_get_option",
            "pe_score_blocks", "pe_prefill_prune", "pe_evict_blocks", "pe_paged_decode", "pe_append_kv",

@@ -28,7 +28,6 @@
 namespace pe {
 namespace {
 
-constexpr int kLoadsPerTile = 4;
 constexpr float kNegInf = -__builtin_inff();
 
 constexpr int next_pow2(int x) { return x <= 1 ? 1 : 2 * next_pow2((x + 1) / 2); }
@@ -161,13 +160,13 @@ struct DecodeParams {
   int n_spare;
 };
 
-template <typename T, int D, int G>
+template <typename T, int D, int G, int LOADS>
 struct Tile {
   using Geo = RowGeom<T, D>;
   static constexpr int EPL = Geo::kPerVec;
   static constexpr int LPR = Geo::kLanesPerRow;
   static constexpr int TPL = Geo::kTokensPerLoad;
-  static constexpr int NLT = kLoadsPerTile;
+  static constexpr int NLT = LOADS;  // wave-loads of K (and of V) per tile
   static constexpr int TT = NLT * TPL;  // tokens per tile
   static constexpr int GP = next_pow2(G);
   static_assert(GP <= LPR && GP <= 8, "query group too large");
@@ -262,9 +261,9 @@ struct Tile {
   }
 };
 
-template <typename T, int D, int G, int WAVES, int DEPTH, bool FUSED>
+template <typename T, int D, int G, int WAVES, int DEPTH, int LOADS, bool FUSED>
 __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const DecodeParams p) {
-  using TL = Tile<T, D, G>;
+  using TL = Tile<T, D, G, LOADS>;
   constexpr int EPL = TL::EPL, LPR = TL::LPR, TPL = TL::TPL, NLT = TL::NLT, TT = TL::TT, GP = TL::GP;
   constexpr int GBITS = ilog2(GP);
   constexpr int NCONTRIB = WAVES * TPL;
@@ -494,7 +493,7 @@ __global__ __launch_bounds__(D) void paged_decode_reduce_kernel(const float* __r
   }
 }
 
-template <typename T, int D, int G, int WAVES, int DEPTH>
+template <typename T, int D, int G, int WAVES, int DEPTH, int LOADS>
 hipError_t launch_one(const DecodeArgs& a, hipStream_t stream) {
   DecodeParams p;
   p.q = a.q;
@@ -523,10 +522,10 @@ hipError_t launch_one(const DecodeArgs& a, hipStream_t stream) {
   const int64_t grid = rows * a.splits;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   if (a.new_k != nullptr) {
-    hipLaunchKernelGGL((paged_decode_kernel<T, D, G, WAVES, DEPTH, true>), dim3((unsigned)grid), dim3(WAVES * kWave), 0,
+    hipLaunchKernelGGL((paged_decode_kernel<T, D, G, WAVES, DEPTH, LOADS, true>), dim3((unsigned)grid), dim3(WAVES * kWave), 0,
                        stream, p);
   } else {
-    hipLaunchKernelGGL((paged_decode_kernel<T, D, G, WAVES, DEPTH, false>), dim3((unsigned)grid), dim3(WAVES * kWave),
+    hipLaunchKernelGGL((paged_decode_kernel<T, D, G, WAVES, DEPTH, LOADS, false>), dim3((unsigned)grid), dim3(WAVES * kWave),
                        0, stream, p);
   }
   hipError_t e = hipGetLastError();
@@ -536,17 +535,23 @@ hipError_t launch_one(const DecodeArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// Workgroup shape: four waves, two register buffers, two wave-loads of K and of V per tile (4 KiB per tile,
+// 8 KiB per wave in flight while it waits).  On an MI355X the stream runs fastest at about 8 MiB in flight
+// over the chip: measured on the headline shape 45.0 us per launch against 46.8 (4 loads per tile),
+// 45.9 (three buffers), 47.3 (eight waves) and 62 (one load per tile).  The other shapes are selectable
+// for tuning on the headline instantiation only.
 template <typename T, int D, int G>
 hipError_t launch_variant(const DecodeArgs& a, hipStream_t stream) {
-  if constexpr (sizeof(T) == 2 && D == 128 && G == 4) {  // tuning variants for the headline shape
-    switch (a.waves * 10 + a.depth) {
-      case 42: return launch_one<T, D, G, 4, 2>(a, stream);
-      case 43: return launch_one<T, D, G, 4, 3>(a, stream);
-      case 82: return launch_one<T, D, G, 8, 2>(a, stream);
+  if constexpr (sizeof(T) == 2 && D == 128 && G == 4) {
+    switch (a.waves * 100 + a.depth * 10 + a.loads) {
+      case 422: return launch_one<T, D, G, 4, 2, 2>(a, stream);
+      case 424: return launch_one<T, D, G, 4, 2, 4>(a, stream);
+      case 432: return launch_one<T, D, G, 4, 3, 2>(a, stream);
+      case 822: return launch_one<T, D, G, 8, 2, 2>(a, stream);
       default: return hipErrorInvalidValue;
     }
   } else {
-    return launch_one<T, D, G, 4, 2>(a, stream);
+    return launch_one<T, D, G, 4, 2, 2>(a, stream);
   }
 }
 

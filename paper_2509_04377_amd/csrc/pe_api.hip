@@ -7,7 +7,7 @@
 namespace {
 
 int g_options[PE_OPT_COUNT_] = {0 /* decode splits: auto */, 1 /* XCD-aware workgroup order */, 4 /* waves */,
-                                2 /* pipeline depth */};
+                                2 /* pipeline depth */, 2 /* loads per tile */};
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -70,8 +70,9 @@ int pe_set_option(int key, int value) {
   if (key < 0 || key >= PE_OPT_COUNT_) return PE_ERR_INVALID_ARG;
   if (key == PE_OPT_DECODE_SPLITS && (value < 0 || value > 256)) return PE_ERR_INVALID_ARG;
   if (key == PE_OPT_DECODE_XCD_MAP && value != 0 && value != 1) return PE_ERR_INVALID_ARG;
-  if (key == PE_OPT_DECODE_WAVES && value != 4 && value != 8 && value != 16) return PE_ERR_INVALID_ARG;
-  if (key == PE_OPT_DECODE_DEPTH && (value < 2 || value > 4)) return PE_ERR_INVALID_ARG;
+  if (key == PE_OPT_DECODE_WAVES && value != 4 && value != 8) return PE_ERR_INVALID_ARG;
+  if (key == PE_OPT_DECODE_DEPTH && (value < 2 || value > 3)) return PE_ERR_INVALID_ARG;
+  if (key == PE_OPT_DECODE_LOADS && value != 2 && value != 4) return PE_ERR_INVALID_ARG;
   g_options[key] = value;
   return PE_OK;
 }
@@ -253,6 +254,7 @@ int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool
   a.xcd_map = g_options[PE_OPT_DECODE_XCD_MAP];
   a.waves = g_options[PE_OPT_DECODE_WAVES];
   a.depth = g_options[PE_OPT_DECODE_DEPTH];
+  a.loads = g_options[PE_OPT_DECODE_LOADS];
   a.is_bf16 = desc->dtype == PE_BF16;
   return pe::launch_paged_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
@@ -296,6 +298,7 @@ int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const v
   a.xcd_map = g_options[PE_OPT_DECODE_XCD_MAP];
   a.waves = g_options[PE_OPT_DECODE_WAVES];
   a.depth = g_options[PE_OPT_DECODE_DEPTH];
+  a.loads = g_options[PE_OPT_DECODE_LOADS];
   a.is_bf16 = desc->dtype == PE_BF16;
   a.new_k = new_k;
   a.new_v = new_v;

@@ -59,6 +59,7 @@ struct DecodeArgs {
   int splits;
   int xcd_map;
   int waves, depth;  // workgroup size in waves, register pipeline depth
+  int loads = 2;     // wave-loads of K (and of V) per tile
   bool is_bf16;
   // fused append: all null / 0 for plain attention
   const void* new_k = nullptr;
