@@ -271,6 +271,7 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
   constexpr int HC = G < 4 ? G : 4;  // heads merged per LDS pass
   __shared__ float sm_m[NCONTRIB][GP];
   __shared__ float sm_l[NCONTRIB][GP];
+  __shared__ float sm_ML[G][2];
   __shared__ __attribute__((aligned(16))) float sm_acc[NCONTRIB][HC][D];
 
   const int lane = lane_id();
@@ -405,11 +406,25 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
     }
   }
 
-  // ---- merge the WAVES x TPL token streams of this workgroup through LDS, up to four heads per pass ----
+  // ---- merge the WAVES x TPL token streams of this workgroup through LDS ------------------------------
+  // (1) every stream publishes its (m, l) per head; (2) one thread per head folds them into the row's
+  // (M, L); (3) every lane rescales its accumulators to M and publishes them, up to four heads per pass;
+  // (4) all threads sum the streams and write the output (or the split partial).
   const int contrib = wave * TPL + grp;
   if (u < GP) {
     sm_m[contrib][c_lane] = m_run;
     sm_l[contrib][c_lane] = l_run;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < G) {
+    const int h = (int)threadIdx.x;
+    float mm = kNegInf;
+    for (int c = 0; c < NCONTRIB; ++c) mm = fmaxf(mm, sm_m[c][h]);
+    const float ms = mm == kNegInf ? 0.f : mm;
+    float ll = 0.f;
+    for (int c = 0; c < NCONTRIB; ++c) ll = fmaf(sm_l[c][h], __builtin_amdgcn_exp2f(sm_m[c][h] - ms), ll);
+    sm_ML[h][0] = mm;
+    sm_ML[h][1] = ll;
   }
   __syncthreads();
 #pragma unroll
@@ -419,8 +434,7 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
     for (int hh = 0; hh < HC; ++hh) {
       const int h = h0 + hh;
       if (h < G) {
-        float mm = kNegInf;
-        for (int c = 0; c < NCONTRIB; ++c) mm = fmaxf(mm, sm_m[c][h]);
+        const float mm = sm_ML[h][0];
         const float ms = mm == kNegInf ? 0.f : mm;
         const float f = __builtin_amdgcn_exp2f(sm_m[contrib][h] - ms);
         float4* dst = reinterpret_cast<float4*>(&sm_acc[contrib][hh][u * EPL]);
@@ -434,14 +448,10 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
       const int hh = idx / D, d = idx % D;
       const int h = h0 + hh;
       if (h >= p.g_real) continue;
-      float mm = kNegInf;
-      for (int c = 0; c < NCONTRIB; ++c) mm = fmaxf(mm, sm_m[c][h]);
-      const float ms = mm == kNegInf ? 0.f : mm;
-      float ll = 0.f, o = 0.f;
-      for (int c = 0; c < NCONTRIB; ++c) {
-        ll = fmaf(sm_l[c][h], __builtin_amdgcn_exp2f(sm_m[c][h] - ms), ll);
-        o += sm_acc[c][hh][d];
-      }
+      const float mm = sm_ML[h][0], ll = sm_ML[h][1];
+      float o = 0.f;
+#pragma unroll 8
+      for (int c = 0; c < NCONTRIB; ++c) o += sm_acc[c][hh][d];
       if (p.splits == 1) {
         const float r = ll > 0.f ? o / ll : 0.f;
         const int64_t off = ((int64_t)s * p.num_q_heads + hk * p.g_real + h) * D + d;
