@@ -110,6 +110,22 @@ def _check(status, where):
         raise PeError(status, where)
 
 
+class _HostOnly:
+    """While active, the kernel-launching wrappers below return without calling the library, so a driver can
+    advance its host-side bookkeeping for a step whose launches are replayed from a captured HIP graph."""
+    active = False
+
+    def __enter__(self):
+        _HostOnly.active = True
+
+    def __exit__(self, *exc):
+        _HostOnly.active = False
+
+
+def host_only():
+    return _HostOnly()
+
+
 def _ptr(t, name, dtype=None, optional=False):
     if t is None:
         if optional:
@@ -147,6 +163,8 @@ def alloc_workspace(op: int, desc: pe_cache_desc, total_tokens: int = 0, device=
 
 
 def pe_score_blocks(desc, k_pool, v_pool, block_table, seq_lens, scores_out, workspace=None):
+    if _HostOnly.active:
+        return
     wp, wn = _ws(workspace)
     _check(lib().pe_score_blocks(ctypes.byref(desc), _ptr(k_pool, "k_pool"), _ptr(v_pool, "v_pool"),
                                  _ptr(block_table, "block_table", torch.int32), _ptr(seq_lens, "seq_lens", torch.int32),
@@ -155,6 +173,8 @@ def pe_score_blocks(desc, k_pool, v_pool, block_table, seq_lens, scores_out, wor
 
 def pe_prefill_prune(desc, k_in, v_in, cu_seqlens, total_tokens, max_seqlen, budget_tokens, k_pool, v_pool,
                      block_table, seq_lens_out, kept_idx_out, workspace):
+    if _HostOnly.active:
+        return
     wp, wn = _ws(workspace)
     _check(lib().pe_prefill_prune(ctypes.byref(desc), _ptr(k_in, "k_in"), _ptr(v_in, "v_in"),
                                   _ptr(cu_seqlens, "cu_seqlens", torch.int32), int(total_tokens), int(max_seqlen),
@@ -166,6 +186,8 @@ def pe_prefill_prune(desc, k_in, v_in, cu_seqlens, total_tokens, max_seqlen, bud
 
 
 def pe_evict_blocks(desc, scores, block_table, seq_lens, budget_tokens, evicted_logical_out, freed_phys_out):
+    if _HostOnly.active:
+        return
     _check(lib().pe_evict_blocks(ctypes.byref(desc), _ptr(scores, "scores", torch.float32),
                                  _ptr(block_table, "block_table", torch.int32), _ptr(seq_lens, "seq_lens", torch.int32),
                                  int(budget_tokens), _ptr(evicted_logical_out, "evicted_logical_out", torch.int32),
@@ -173,6 +195,8 @@ def pe_evict_blocks(desc, scores, block_table, seq_lens, budget_tokens, evicted_
 
 
 def pe_score_recent_blocks(desc, k_pool, v_pool, block_table, seq_lens, recent, scores_inout):
+    if _HostOnly.active:
+        return
     _check(lib().pe_score_recent_blocks(ctypes.byref(desc), _ptr(k_pool, "k_pool"), _ptr(v_pool, "v_pool"),
                                         _ptr(block_table, "block_table", torch.int32),
                                         _ptr(seq_lens, "seq_lens", torch.int32), int(recent),
@@ -182,6 +206,8 @@ def pe_score_recent_blocks(desc, k_pool, v_pool, block_table, seq_lens, recent, 
 
 def pe_evict_blocks_cached(desc, scores_inout, block_table, seq_lens, budget_tokens, evicted_logical_out,
                            freed_phys_out):
+    if _HostOnly.active:
+        return
     _check(lib().pe_evict_blocks_cached(ctypes.byref(desc), _ptr(scores_inout, "scores_inout", torch.float32),
                                         _ptr(block_table, "block_table", torch.int32),
                                         _ptr(seq_lens, "seq_lens", torch.int32), int(budget_tokens),
@@ -191,6 +217,8 @@ def pe_evict_blocks_cached(desc, scores_inout, block_table, seq_lens, budget_tok
 
 
 def pe_paged_decode(desc, q, k_pool, v_pool, block_table, seq_lens, softmax_scale, out, workspace=None):
+    if _HostOnly.active:
+        return
     wp, wn = _ws(workspace)
     _check(lib().pe_paged_decode(ctypes.byref(desc), _ptr(q, "q"), _ptr(k_pool, "k_pool"), _ptr(v_pool, "v_pool"),
                                  _ptr(block_table, "block_table", torch.int32), _ptr(seq_lens, "seq_lens", torch.int32),
@@ -198,6 +226,8 @@ def pe_paged_decode(desc, q, k_pool, v_pool, block_table, seq_lens, softmax_scal
 
 
 def pe_append_kv(desc, new_k, new_v, k_pool, v_pool, block_table, seq_lens, freed_phys, spare, spare_used):
+    if _HostOnly.active:
+        return
     _check(lib().pe_append_kv(ctypes.byref(desc), _ptr(new_k, "new_k"), _ptr(new_v, "new_v"), _ptr(k_pool, "k_pool"),
                               _ptr(v_pool, "v_pool"), _ptr(block_table, "block_table", torch.int32),
                               _ptr(seq_lens, "seq_lens", torch.int32), _ptr(freed_phys, "freed_phys", torch.int32),
@@ -207,6 +237,8 @@ def pe_append_kv(desc, new_k, new_v, k_pool, v_pool, block_table, seq_lens, free
 
 def pe_append_paged_decode(desc, new_k, new_v, q, k_pool, v_pool, block_table, seq_lens, seq_lens_out, freed_phys, spare,
                            spare_used, softmax_scale, out, workspace=None):
+    if _HostOnly.active:
+        return
     wp, wn = _ws(workspace)
     _check(lib().pe_append_paged_decode(ctypes.byref(desc), _ptr(new_k, "new_k"), _ptr(new_v, "new_v"), _ptr(q, "q"),
                                         _ptr(k_pool, "k_pool"), _ptr(v_pool, "v_pool"),

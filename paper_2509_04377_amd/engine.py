@@ -74,3 +74,42 @@ class LayeredCache:
             self.folded.seq_lens, self.folded.seq_lens_alt = self.folded.seq_lens_alt, self.folded.seq_lens
         self.host_lens = [n + 1 for n in self.host_lens]
         return any(trig)
+
+
+class GraphedStepper:
+    """Replays the launches of a decode step from captured HIP graphs (one per distinct launch sequence).
+
+    The inputs live in fixed buffers (new_k, new_v, q, out), as a serving loop would keep them.  A step's
+    launch sequence depends only on host-side integers (which lengths array is current, whether this is a
+    trigger step, how many pages the cached-score mode has to score), so that tuple keys the graph.  The
+    first step with a new key is captured and then replayed; later ones advance the host bookkeeping with
+    the launches switched off and replay the stored graph."""
+
+    def __init__(self, eng: "LayeredCache", new_k, new_v, q, out, softmax_scale: Optional[float] = None):
+        self.eng, self.args = eng, (new_k, new_v, q, out, softmax_scale)
+        self.graphs = {}
+
+    def _key(self):
+        e, f = self.eng, self.eng.folded
+        trig = any(e._triggers())
+        recent = None
+        if trig and f.cached_scores:
+            if f.host_scored is None:
+                recent = -1
+            else:
+                recent = max(n // e.B - sc for n, sc in zip(e.host_lens * e.layers, f.host_scored))
+        return (f.seq_lens.data_ptr(), trig, e.fused, f.cached_scores, recent)
+
+    def step(self) -> bool:
+        key = self._key()
+        g = self.graphs.get(key)
+        if g is None:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                trig = self.eng.decode_step(*self.args)
+            self.graphs[key] = g
+        else:
+            with pe.host_only():
+                trig = self.eng.decode_step(*self.args)
+        g.replay()
+        return trig
