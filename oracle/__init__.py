@@ -39,6 +39,8 @@ def _load():
                                              [_f32p, _f32p, _i32p, _i32p, _i32p, _f32p])
         lib.oracle_evict_blocks.restype = ctypes.c_int
         lib.oracle_evict_blocks.argtypes = [_f32p, _i32p, _i32p] + [ctypes.c_int] * 5 + [_i32p, _i32p]
+        lib.oracle_evict_blocks_ex.restype = ctypes.c_int
+        lib.oracle_evict_blocks_ex.argtypes = [_f32p, _i32p, _i32p] + [ctypes.c_int] * 9 + [_i32p, _i32p]
         lib.oracle_append_kv.restype = ctypes.c_int
         lib.oracle_append_kv.argtypes = ([_f32p, _f32p, _f32p, _f32p, _i32p, _i32p, _i32p, _i32p, _i32p] +
                                          [ctypes.c_int] * 6)
@@ -140,6 +142,30 @@ def evict_blocks(scores, block_table, seq_lens, block_size, budget):
                                      int(block_size), mb, int(budget), _p(ev, _i32p), _p(fr, _i32p))
     if rc != 0:
         raise ValueError("oracle_evict_blocks failed with status %d" % rc)
+    return ev, fr
+
+
+POLICY_LOWEST_SCORE, POLICY_OLDEST = 0, 1
+
+
+def evict_blocks_ex(scores, block_table, seq_lens, block_size, budget, policy=POLICY_LOWEST_SCORE, protect_first=0,
+                    protect_last=0, share_heads=False):
+    """Eviction with a policy, protected pages and optionally one decision per sequence.  In place on
+    block_table / seq_lens.  `scores` may be None for POLICY_OLDEST.  Returns (evicted_logical, freed_phys)."""
+    S, Hk, mb = block_table.shape
+    assert block_table.dtype == np.int32 and block_table.flags.c_contiguous
+    assert seq_lens.dtype == np.int32 and seq_lens.flags.c_contiguous
+    if scores is not None:
+        scores = _f32(scores)
+        assert scores.shape == (S, Hk, mb)
+    ev = np.empty((S, Hk), dtype=np.int32)
+    fr = np.empty((S, Hk), dtype=np.int32)
+    rc = _load().oracle_evict_blocks_ex(_p(scores, _f32p) if scores is not None else None, _p(block_table, _i32p),
+                                        _p(seq_lens, _i32p), S, Hk, int(block_size), mb, int(budget), int(policy),
+                                        int(protect_first), int(protect_last), int(bool(share_heads)), _p(ev, _i32p),
+                                        _p(fr, _i32p))
+    if rc != 0:
+        raise ValueError("oracle_evict_blocks_ex failed with status %d" % rc)
     return ev, fr
 
 

@@ -211,6 +211,68 @@ int oracle_evict_blocks(const float* scores, int32_t* block_table, int32_t* seq_
   return ORACLE_OK;
 }
 
+/* Variants of the eviction on the same table machinery (not the paper's main method; Sec. 5.2 and
+ * App. A describe StreamingLLM, which keeps a few first tokens as attention sinks plus a window of the
+ * most recent ones; Sec. 2.4 leaves open whether heads decide separately):
+ *   policy 0  lowest score (as above);  policy 1  oldest page (sliding window, scores unused);
+ *   protect_first / protect_last  pages at the start / end of a row that are never candidates;
+ *   share_heads != 0  one decision per sequence: the page score is the mean over the sequence's KV
+ *                     heads of the fp32 page scores, summed in head order in fp64 and rounded once
+ *                     to fp32, and every head of the sequence drops the same logical page.
+ * Candidates are the logical pages lo .. hi-1 with lo = min(protect_first, n-1) and
+ * hi = max(n - protect_last, lo + 1): protection yields before the budget does, so there is always
+ * one candidate.  Ties go to the lowest index.  Everything else is as in oracle_evict_blocks. */
+int oracle_evict_blocks_ex(const float* scores, int32_t* block_table, int32_t* seq_lens, int S, int Hk, int B,
+                           int max_blocks, int C, int policy, int protect_first, int protect_last,
+                           int share_heads, int32_t* evicted_logical_out, int32_t* freed_phys_out) {
+  if (C <= 0 || C % B != 0) return ORACLE_ERR_ARG;
+  if (policy < 0 || policy > 1 || protect_first < 0 || protect_last < 0) return ORACLE_ERR_ARG;
+  if (policy == 0 && scores == NULL) return ORACLE_ERR_ARG;
+  for (int s = 0; s < S; ++s) {
+    const int len = seq_lens[s];
+    const int trigger = (len > 0) && (len % B == 0) && (len >= C);
+    const int n = len / B;
+    int lo = 0, hi = 0;
+    if (trigger) {
+      lo = protect_first < n - 1 ? protect_first : n - 1;
+      hi = n - protect_last > lo + 1 ? n - protect_last : lo + 1;
+    }
+    for (int h = 0; h < Hk; ++h) {
+      const int row = s * Hk + h;
+      if (!trigger) {
+        evicted_logical_out[row] = -1;
+        freed_phys_out[row] = -1;
+        continue;
+      }
+      int best = lo;
+      if (policy == 0) {
+        float best_score = 0.0f;
+        for (int j = lo; j < hi; ++j) {
+          float sc;
+          if (share_heads) {
+            double sum = 0.0;
+            for (int g = 0; g < Hk; ++g) sum += (double)scores[((int64_t)s * Hk + g) * max_blocks + j];
+            sc = (float)(sum / (double)Hk);
+          } else {
+            sc = scores[(int64_t)row * max_blocks + j];
+          }
+          if (j == lo || sc < best_score) { /* strict "<": ties stay with the lowest index */
+            best = j;
+            best_score = sc;
+          }
+        }
+      }
+      int32_t* bt = block_table + (int64_t)row * max_blocks;
+      evicted_logical_out[row] = best;
+      freed_phys_out[row] = bt[best];
+      for (int j = best; j + 1 < n; ++j) bt[j] = bt[j + 1];
+      bt[n - 1] = -1;
+    }
+    if (trigger) seq_lens[s] = len - B;
+  }
+  return ORACLE_OK;
+}
+
 /* Harness step between eviction and attention: the new token's K/V row of every (s, hk)
  * goes to slot len % B of the tail page.  When len % B == 0 a new page is linked in at
  * logical index len / B: the page this row freed in the eviction just before
