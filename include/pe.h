@@ -160,6 +160,30 @@ int pe_evict_blocks_cached(const pe_cache_desc* desc, float* scores_inout, int32
                            void* stream);
 
 /*
+ * Eviction variants on the same table machinery (not the paper's main method).  Sec. 5.2 / App. A describe
+ * StreamingLLM (a few first tokens kept as attention sinks plus a window of the most recent ones); Sec. 2.4
+ * leaves open whether heads decide separately.  opts->policy: PE_POLICY_LOWEST_SCORE (as (3)) or
+ * PE_POLICY_OLDEST (the oldest unprotected page goes; `scores` may be NULL).  protect_first / protect_last:
+ * pages at the start / end of a row that are never candidates.  Candidates are logical pages lo .. hi-1 with
+ * lo = min(protect_first, n-1), hi = max(n - protect_last, lo + 1): protection yields before the budget
+ * does.  share_heads != 0: one decision per sequence; the page score is the mean over the sequence's KV
+ * heads of the fp32 page scores (summed in head order in fp64, rounded once) and every head drops the same
+ * logical page.  cached_scores != 0: `scores` is in/out and entry j* is deleted from each score row as in
+ * pe_evict_blocks_cached.  Trigger, tie-break (lowest index), outputs and in-place updates are as in (3).
+ */
+typedef enum { PE_POLICY_LOWEST_SCORE = 0, PE_POLICY_OLDEST = 1 } pe_evict_policy;
+typedef struct pe_evict_opts {
+  int32_t policy;
+  int32_t protect_first;
+  int32_t protect_last;
+  int32_t share_heads;
+  int32_t cached_scores;
+} pe_evict_opts;
+int pe_evict_blocks_ex(const pe_cache_desc* desc, const pe_evict_opts* opts, float* scores, int32_t* block_table,
+                       int32_t* seq_lens, int32_t budget_tokens, int32_t* evicted_logical_out,
+                       int32_t* freed_phys_out, void* stream);
+
+/*
  * (4) Paged decode attention -- Eq. 1 for one new query per sequence; Alg. 3 "PagedAttention(Q,K,V)".
  *     out[s][h][:] = sum_t softmax_t(softmax_scale * <q[s][h], K_t>) V_t over the seq_lens[s] tokens of
  *     row (s, h / (Hq/Hk)), token t being slot t % B of page block_table[s][hk][t / B].

@@ -11,7 +11,7 @@ from dataclasses import dataclass
 
 import numpy as np
 
-from . import append_kv, evict_blocks, paged_decode, score_blocks
+from . import POLICY_OLDEST, append_kv, evict_blocks, evict_blocks_ex, paged_decode, score_blocks
 
 
 @dataclass
@@ -30,15 +30,22 @@ class OracleCache:
         return self.k_pool.shape[1]
 
 
-def decode_step(cache: OracleCache, new_k, new_v, q, scale=None):
+def decode_step(cache: OracleCache, new_k, new_v, q, scale=None, evict_opts=None):
     """Runs (i)-(iii) in place on `cache`.  Returns (out fp64, scores, evicted_logical, freed_phys);
     scores is None on a step where no sequence's newest page has just filled at budget (Alg. 3 scores
-    pages only inside its "L % B == 0" branch)."""
+    pages only inside its "L % B == 0" branch).  `evict_opts` (policy, protect_first, protect_last,
+    share_heads) selects an eviction variant; None is the paper's lowest-score rule."""
     B, C = cache.block_size, cache.budget
     lens = cache.seq_lens
     if np.any((lens > 0) & (lens % B == 0) & (lens >= C)):
-        scores = score_blocks(cache.k_pool, cache.v_pool, cache.block_table, cache.seq_lens)
-        evicted, freed = evict_blocks(scores, cache.block_table, cache.seq_lens, B, C)
+        if evict_opts is None:
+            scores = score_blocks(cache.k_pool, cache.v_pool, cache.block_table, cache.seq_lens)
+            evicted, freed = evict_blocks(scores, cache.block_table, cache.seq_lens, B, C)
+        else:
+            scores = None
+            if evict_opts.get("policy", 0) != POLICY_OLDEST:
+                scores = score_blocks(cache.k_pool, cache.v_pool, cache.block_table, cache.seq_lens)
+            evicted, freed = evict_blocks_ex(scores, cache.block_table, cache.seq_lens, B, C, **evict_opts)
     else:
         scores = None
         evicted = np.full(cache.freed_phys.shape, -1, np.int32)

@@ -24,13 +24,21 @@ PE_OPT_DECODE_LOADS = 4
 
 EXPORTS = ["pe_workspace_bytes", "pe_status_string", "pe_version", "pe_set_option", "pe_get_option",
            "pe_score_blocks", "pe_prefill_prune", "pe_evict_blocks", "pe_paged_decode", "pe_append_kv",
-           "pe_append_paged_decode", "pe_score_recent_blocks", "pe_evict_blocks_cached"]
+           "pe_append_paged_decode", "pe_score_recent_blocks", "pe_evict_blocks_cached", "pe_evict_blocks_ex"]
 
 
 class pe_cache_desc(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("num_seqs", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
                 ("num_q_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32),
                 ("max_blocks", ctypes.c_int32), ("num_phys_blocks", ctypes.c_int64)]
+
+
+class pe_evict_opts(ctypes.Structure):
+    _fields_ = [("policy", ctypes.c_int32), ("protect_first", ctypes.c_int32), ("protect_last", ctypes.c_int32),
+                ("share_heads", ctypes.c_int32), ("cached_scores", ctypes.c_int32)]
+
+
+PE_POLICY_LOWEST_SCORE, PE_POLICY_OLDEST = 0, 1
 
 
 class PeError(RuntimeError):
@@ -75,6 +83,8 @@ def lib():
         L.pe_append_paged_decode.restype = ctypes.c_int
         L.pe_append_paged_decode.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ctypes.c_float, vp, vp, sz,
                                              vp]
+        L.pe_evict_blocks_ex.restype = ctypes.c_int
+        L.pe_evict_blocks_ex.argtypes = [dp, ctypes.POINTER(pe_evict_opts), vp, vp, vp, i32, vp, vp, vp]
         L.pe_score_recent_blocks.restype = ctypes.c_int
         L.pe_score_recent_blocks.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp]
         L.pe_evict_blocks_cached.restype = ctypes.c_int
@@ -216,6 +226,18 @@ def pe_evict_blocks_cached(desc, scores_inout, block_table, seq_lens, budget_tok
            "pe_evict_blocks_cached")
 
 
+def pe_evict_blocks_ex(desc, opts, scores, block_table, seq_lens, budget_tokens, evicted_logical_out, freed_phys_out):
+    if _HostOnly.active:
+        return
+    _check(lib().pe_evict_blocks_ex(ctypes.byref(desc), ctypes.byref(opts),
+                                    _ptr(scores, "scores", torch.float32, optional=True),
+                                    _ptr(block_table, "block_table", torch.int32),
+                                    _ptr(seq_lens, "seq_lens", torch.int32), int(budget_tokens),
+                                    _ptr(evicted_logical_out, "evicted_logical_out", torch.int32),
+                                    _ptr(freed_phys_out, "freed_phys_out", torch.int32), _stream()),
+           "pe_evict_blocks_ex")
+
+
 def pe_paged_decode(desc, q, k_pool, v_pool, block_table, seq_lens, softmax_scale, out, workspace=None):
     if _HostOnly.active:
         return
@@ -272,6 +294,7 @@ class PagedCache:
     seq_lens_alt: torch.Tensor = None  # second lengths array for pe_append_paged_decode (swapped after each call)
     cached_scores: bool = False    # keep `scores` alive across steps and score only newly filled pages
     host_scored: list = None       # per sequence: full pages whose score is in `scores` (host bookkeeping)
+    evict_opts: pe_evict_opts = None  # eviction variant (policy, protected pages, shared heads); None = Alg. 3
 
     @staticmethod
     def create(dtype, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, layout, budget, device="cuda",
@@ -344,6 +367,14 @@ class PagedCache:
         """Score + evict of a trigger step.  With cached scores only the pages filled since the last call are
         scored (all of them the first time) and the eviction keeps the score rows aligned with the table."""
         B = self.desc.block_size
+        if self.evict_opts is not None:
+            o = self.evict_opts
+            opts = pe_evict_opts(o.policy, o.protect_first, o.protect_last, o.share_heads, 0)
+            if o.policy != PE_POLICY_OLDEST:
+                self.score_blocks()
+            pe_evict_blocks_ex(self.desc, opts, self.scores if o.policy != PE_POLICY_OLDEST else None,
+                               self.block_table, self.seq_lens, self.budget, self.evicted_logical, self.freed_phys)
+            return
         if not self.cached_scores:
             self.score_blocks()
             self.evict_blocks()

@@ -33,29 +33,29 @@ __global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* sco
                                                                 int32_t* __restrict__ seq_lens,
                                                                 int32_t* __restrict__ evicted_logical,
                                                                 int32_t* __restrict__ freed_phys, int num_kv_heads,
-                                                                int block_size, int max_blocks, int budget) {
+                                                                int block_size, int max_blocks, int budget,
+                                                                int policy, int protect_first, int protect_last,
+                                                                int share_heads) {
   const int s = (int)blockIdx.x;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   const int len = seq_lens[s];
   const bool trigger = len > 0 && (len % block_size) == 0 && len >= budget;
   const int n = len / block_size;
+  // candidate pages lo .. hi-1: protection yields before the budget does (always one candidate)
+  const int lo = protect_first < n - 1 ? protect_first : n - 1;
+  const int hi = n - protect_last > lo + 1 ? n - protect_last : lo + 1;
 
-  for (int h = wave; h < num_kv_heads; h += kWaves) {
-    const int64_t row = (int64_t)s * num_kv_heads + h;
-    if (!trigger) {
-      if (lane == 0) {
-        evicted_logical[row] = -1;
-        freed_phys[row] = -1;
-      }
-      continue;
-    }
-    const float* sc_row = scores + row * max_blocks;
-    int32_t* bt = block_table + row * max_blocks;
+  // One decision per sequence: every wave computes the same argmin over head-averaged scores (mean over
+  // the KV heads in fp64, head order, one rounding to fp32) BEFORE any wave touches a score row.
+  int j_shared = lo;
+  if (trigger && policy == 0 && share_heads) {
     float best = __builtin_inff();
     int best_j = 0x7fffffff;
-    for (int j = lane; j < n; j += kWave) {
-      const float v = sc_row[j];
+    for (int j = lo + lane; j < hi; j += kWave) {
+      double sum = 0.0;
+      for (int g = 0; g < num_kv_heads; ++g) sum += (double)scores[((int64_t)s * num_kv_heads + g) * max_blocks + j];
+      const float v = (float)(sum / (double)num_kv_heads);
       if (v < best || (v == best && j < best_j)) {
         best = v;
         best_j = j;
@@ -67,7 +67,40 @@ __global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* sco
     min_step<8>(best, best_j);
     min_step<16>(best, best_j);
     min_step<32>(best, best_j);
-    const int jstar = __builtin_amdgcn_readfirstlane(best_j);
+    j_shared = __builtin_amdgcn_readfirstlane(best_j);
+  }
+  if (share_heads) __syncthreads();
+
+  for (int h = wave; h < num_kv_heads; h += kWaves) {
+    const int64_t row = (int64_t)s * num_kv_heads + h;
+    if (!trigger) {
+      if (lane == 0) {
+        evicted_logical[row] = -1;
+        freed_phys[row] = -1;
+      }
+      continue;
+    }
+    int32_t* bt = block_table + row * max_blocks;
+    int jstar = j_shared;  // policy 1 (oldest unprotected page) and shared decisions are already known
+    if (policy == 0 && !share_heads) {
+      const float* sc_row = scores + row * max_blocks;
+      float best = __builtin_inff();
+      int best_j = 0x7fffffff;
+      for (int j = lo + lane; j < hi; j += kWave) {
+        const float v = sc_row[j];
+        if (v < best || (v == best && j < best_j)) {
+          best = v;
+          best_j = j;
+        }
+      }
+      min_step<1>(best, best_j);
+      min_step<2>(best, best_j);
+      min_step<4>(best, best_j);
+      min_step<8>(best, best_j);
+      min_step<16>(best, best_j);
+      min_step<32>(best, best_j);
+      jstar = __builtin_amdgcn_readfirstlane(best_j);
+    }
     const int freed = bt[jstar];
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_s_waitcnt(0);  // the evicted entry has been read before any store below is issued
@@ -149,7 +182,7 @@ __global__ __launch_bounds__(kThreads) void append_kv_kernel(const uint4* __rest
 hipError_t launch_evict_blocks(const EvictArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL(evict_blocks_kernel, dim3((unsigned)a.num_seqs), dim3(kThreads), 0, stream, a.scores,
                      a.scores_mut, a.block_table, a.seq_lens, a.evicted_logical, a.freed_phys, a.num_kv_heads, a.block_size,
-                     a.max_blocks, a.budget);
+                     a.max_blocks, a.budget, a.policy, a.protect_first, a.protect_last, a.share_heads);
   return hipGetLastError();
 }
 

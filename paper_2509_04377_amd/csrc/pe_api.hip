@@ -182,7 +182,19 @@ int pe_prefill_prune(const pe_cache_desc* desc, const void* k_in, const void* v_
 namespace {
 int evict_blocks_impl(const pe_cache_desc* desc, const float* scores, float* scores_mut, int32_t* block_table,
                       int32_t* seq_lens, int32_t budget_tokens, int32_t* evicted_logical_out, int32_t* freed_phys_out,
-                      void* stream);
+                      void* stream, const pe_evict_opts* opts = nullptr);
+}
+
+int pe_evict_blocks_ex(const pe_cache_desc* desc, const pe_evict_opts* opts, float* scores, int32_t* block_table,
+                       int32_t* seq_lens, int32_t budget_tokens, int32_t* evicted_logical_out,
+                       int32_t* freed_phys_out, void* stream) {
+  if (opts == nullptr) return PE_ERR_INVALID_ARG;
+  if (opts->policy != PE_POLICY_LOWEST_SCORE && opts->policy != PE_POLICY_OLDEST) return PE_ERR_INVALID_ARG;
+  if (opts->protect_first < 0 || opts->protect_last < 0) return PE_ERR_INVALID_ARG;
+  if (opts->policy == PE_POLICY_LOWEST_SCORE && scores == nullptr) return PE_ERR_INVALID_ARG;
+  if (opts->cached_scores && scores == nullptr) return PE_ERR_INVALID_ARG;
+  return evict_blocks_impl(desc, scores, opts->cached_scores ? scores : nullptr, block_table, seq_lens, budget_tokens,
+                           evicted_logical_out, freed_phys_out, stream, opts);
 }
 
 int pe_evict_blocks(const pe_cache_desc* desc, const float* scores, int32_t* block_table, int32_t* seq_lens,
@@ -201,10 +213,10 @@ int pe_evict_blocks_cached(const pe_cache_desc* desc, float* scores_inout, int32
 namespace {
 int evict_blocks_impl(const pe_cache_desc* desc, const float* scores, float* scores_mut, int32_t* block_table,
                       int32_t* seq_lens, int32_t budget_tokens, int32_t* evicted_logical_out, int32_t* freed_phys_out,
-                      void* stream) {
+                      void* stream, const pe_evict_opts* opts) {
   const int st = check_desc(desc);
   if (st != PE_OK) return st;
-  if (!scores || !block_table || !seq_lens || !evicted_logical_out || !freed_phys_out) return PE_ERR_INVALID_ARG;
+  if ((!scores && !(opts && opts->policy == PE_POLICY_OLDEST)) || !block_table || !seq_lens || !evicted_logical_out || !freed_phys_out) return PE_ERR_INVALID_ARG;
   if (budget_tokens <= 0 || budget_tokens % desc->block_size != 0) return PE_ERR_INVALID_ARG;
   pe::EvictArgs a;
   a.scores = scores;
@@ -218,6 +230,12 @@ int evict_blocks_impl(const pe_cache_desc* desc, const float* scores, float* sco
   a.block_size = desc->block_size;
   a.max_blocks = desc->max_blocks;
   a.budget = budget_tokens;
+  if (opts != nullptr) {
+    a.policy = opts->policy;
+    a.protect_first = opts->protect_first;
+    a.protect_last = opts->protect_last;
+    a.share_heads = opts->share_heads != 0;
+  }
   return pe::launch_evict_blocks(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
 }  // namespace

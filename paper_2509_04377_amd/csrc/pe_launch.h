@@ -28,6 +28,7 @@ struct EvictArgs {
   int32_t* evicted_logical;
   int32_t* freed_phys;
   int num_seqs, num_kv_heads, block_size, max_blocks, budget;
+  int policy = 0, protect_first = 0, protect_last = 0, share_heads = 0;
 };
 hipError_t launch_evict_blocks(const EvictArgs& a, hipStream_t stream);
 

@@ -30,7 +30,7 @@ def _compare_state(cache_gpu, cache_cpu, where):
     assert np.array_equal(cache_gpu.spare_used.cpu().numpy(), cache_cpu.spare_used), where
 
 
-def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=False):
+def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=False, evict_opts=None):
     """One layer of workload `wl`: prune, then `steps` decode steps on both sides, compared every step."""
     lens = synth.context_lengths(wl, SEED)
     k_in, v_in, cu = synth.prompt_kv(wl, layer, lens, SEED)
@@ -43,6 +43,9 @@ def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=Fals
     gcache.prefill_prune(k_in.to(DEV), v_in.to(DEV), cu.to(DEV), max(lens), kept)
     gcache.set_host_lens(lens)
     gcache.cached_scores = cached_scores
+    if evict_opts is not None:
+        gcache.evict_opts = pe.pe_evict_opts(evict_opts.get("policy", 0), evict_opts.get("protect_first", 0),
+                                             evict_opts.get("protect_last", 0), int(evict_opts.get("share_heads", False)), 0)
     torch.cuda.synchronize()
     assert np.array_equal(kept.cpu().numpy(), okept)
     _compare_state(gcache, ocache, "after prune")
@@ -55,7 +58,7 @@ def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=Fals
     for step in range(steps):
         nk, nv, q = synth.decode_inputs(wl, layer, step, SEED)
         triggered = gcache.any_trigger()
-        want, oscores, oev, ofr = oracle_step(ocache, f32(nk), f32(nv), f32(q))
+        want, oscores, oev, ofr = oracle_step(ocache, f32(nk), f32(nv), f32(q), evict_opts=evict_opts)
         gcache.evicted_logical.fill_(-1)
         gcache.decode_step(nk.to(DEV), nv.to(DEV), q.to(DEV), out, fused=fused)
         torch.cuda.synchronize()
@@ -65,6 +68,7 @@ def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=Fals
         assert (oev >= 0).any() == triggered, where
         if triggered:
             n_evictions += 1
+        if triggered and oscores is not None:
             gs = gcache.scores.cpu().numpy()
             if cached_scores:   # the kept array has already lost the evicted entry of every row that evicted
                 want_sc = oscores.copy()
@@ -115,6 +119,16 @@ def test_cached_scores_give_the_same_decisions(wl, steps, n_want):
     print("case loop cached scores", wl.name, flush=True)
     n_ev, _ = run_loop(wl, steps, cached_scores=True)
     assert n_ev == n_want
+
+
+@pytest.mark.parametrize("opts", [dict(policy=1, protect_first=1), dict(policy=0, protect_first=1, protect_last=2),
+                                  dict(policy=0, share_heads=True), dict(policy=1)])
+def test_eviction_variants_loop(opts):
+    """Sliding window with a sink page, protected first/last pages, one decision per sequence: the whole
+    loop against the oracle's loop with the same variant, tables bit-exact at every step."""
+    print("case loop variants", opts, flush=True)
+    n_ev, _ = run_loop(synth.TINY.with_(num_seqs=2), 40, evict_opts=opts)
+    assert n_ev == 3
 
 
 def test_tiny_full_cache_never_evicts():

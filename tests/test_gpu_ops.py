@@ -336,3 +336,59 @@ def test_append_paged_decode_fused(dt, D, B, G):
                 assert e2 <= TOL[dt] and emax <= TOL[dt], (step, rep, e2, emax)
     finally:
         pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, 0)
+
+
+@pytest.mark.parametrize("opts", [dict(policy=0, protect_first=2, protect_last=3), dict(policy=1, protect_first=4),
+                                  dict(policy=0, share_heads=True), dict(policy=0, share_heads=True, protect_first=1),
+                                  dict(policy=1), dict(policy=0, protect_first=500)])
+@pytest.mark.parametrize("cached", [False, True])
+def test_evict_blocks_ex_bit_exact(opts, cached):
+    """Eviction variants against the oracle on rows of 1 .. 300 pages with many tied scores; with cached
+    scores the score rows must be compacted exactly like the table rows."""
+    print("case evict_blocks_ex", opts, cached, flush=True)
+    rng = np.random.default_rng(900)
+    B, Hk = 16, 6
+    n_pages = [1, 2, 5, 63, 64, 65, 129, 300, 7, 40, 0]
+    S, mb = len(n_pages), 301
+    lens = np.array([n * B for n in n_pages], np.int32)
+    lens[8] -= 5
+    C = 2 * B
+    scores = (rng.integers(0, 6, size=(S, Hk, mb)) * 0.25 + rng.integers(0, 2, size=(S, Hk, mb)) * 2.0 ** -20
+              ).astype(np.float32)
+    table = np.full((S, Hk, mb), -1, np.int32)
+    ids = rng.permutation(S * Hk * mb).astype(np.int32)
+    pos = 0
+    for s in range(S):
+        n = (lens[s] + B - 1) // B
+        for h in range(Hk):
+            table[s, h, :n] = ids[pos:pos + n]
+            pos += n
+    desc = pe.make_desc(torch.float32, S, Hk, Hk, 64, B, mb, S * Hk * mb)
+    o = pe.pe_evict_opts(opts.get("policy", 0), opts.get("protect_first", 0), opts.get("protect_last", 0),
+                         int(opts.get("share_heads", False)), int(cached))
+    t_gpu, l_gpu = torch.tensor(table, device=DEV), torch.tensor(lens, device=DEV)
+    s_gpu = torch.tensor(scores, device=DEV)
+    ev_gpu = torch.full((S, Hk), -7, dtype=torch.int32, device=DEV)
+    fr_gpu = torch.full((S, Hk), -7, dtype=torch.int32, device=DEV)
+    sc = scores.copy()
+    for call in range(3):
+        n_before = lens // B
+        ev, fr = oracle.evict_blocks_ex(sc, table, lens, B, C, **opts)
+        pe.pe_evict_blocks_ex(desc, o, None if (opts.get("policy", 0) == 1 and not cached) else s_gpu, t_gpu, l_gpu, C,
+                              ev_gpu, fr_gpu)
+        torch.cuda.synchronize()
+        assert np.array_equal(ev_gpu.cpu().numpy(), ev), call
+        assert np.array_equal(fr_gpu.cpu().numpy(), fr), call
+        assert np.array_equal(t_gpu.cpu().numpy(), table), call
+        assert np.array_equal(l_gpu.cpu().numpy(), lens), call
+        if cached:      # delete the evicted entry from the reference score rows as well
+            for s in range(S):
+                for h in range(Hk):
+                    j, n = ev[s, h], n_before[s]
+                    if j >= 0:
+                        sc[s, h, j:n - 1] = sc[s, h, j + 1:n].copy()
+                        sc[s, h, n - 1] = np.inf
+            assert np.array_equal(s_gpu.cpu().numpy().view(np.int32), sc.view(np.int32)), call
+    if opts.get("share_heads"):
+        trig = ev[:, 0] >= 0
+        assert np.all(ev[trig] == ev[trig][:, :1])
