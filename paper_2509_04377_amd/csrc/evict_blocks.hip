@@ -40,8 +40,9 @@ __global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* sco
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   const int len = seq_lens[s];
-  const bool trigger = len > 0 && (len % block_size) == 0 && len >= budget;
   const int n = len / block_size;
+  // a length beyond the table row is a caller error: such a sequence is left alone
+  const bool trigger = len > 0 && (len % block_size) == 0 && len >= budget && n <= max_blocks;
   // candidate pages lo .. hi-1: protection yields before the budget does (always one candidate)
   const int lo = protect_first < n - 1 ? protect_first : n - 1;
   const int hi = n - protect_last > lo + 1 ? n - protect_last : lo + 1;
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(kThreads) void append_kv_kernel(const uint4* __rest
   const int len = seq_lens[s];
   const int slot = len % block_size;
   const int jb = len / block_size;
-  if (jb >= max_blocks) return;  // caller precondition violated: leave everything untouched
+  if (len < 0 || jb >= max_blocks) return;  // caller precondition violated: leave everything untouched
   if (slot == 0) {
     for (int h = (int)threadIdx.x; h < num_kv_heads; h += kThreads) {
       const int64_t row = (int64_t)s * num_kv_heads + h;

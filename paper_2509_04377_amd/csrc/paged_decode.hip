@@ -382,7 +382,7 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
       const int B = 1 << p.log2_block;
       const int slot = len_pool & (B - 1);
       const int jb = len_pool >> p.log2_block;
-      if (jb < p.max_blocks) {
+      if (len_pool >= 0 && jb < p.max_blocks) {  // a length outside the table row is a caller error: touch nothing
         int page;
         if (slot == 0) {
           page = ap_freed;

@@ -39,7 +39,8 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
   const int row = (int)(blockIdx.x / groups_per_row);
   const int grp = (int)(blockIdx.x % groups_per_row);
   const int s = row / num_kv_heads;
-  const int nfull = seq_lens[s] / B;
+  const int nfull_raw = seq_lens[s] / B;
+  const int nfull = nfull_raw < max_blocks ? nfull_raw : max_blocks;  // never index past the table row
   const int32_t* bt = block_table + (int64_t)row * max_blocks;
   float* out = scores + (int64_t)row * max_blocks;
   // recent == 0: every entry of the row; else only the last `recent` full pages

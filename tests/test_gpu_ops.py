@@ -392,3 +392,31 @@ def test_evict_blocks_ex_bit_exact(opts, cached):
     if opts.get("share_heads"):
         trig = ev[:, 0] >= 0
         assert np.all(ev[trig] == ev[trig][:, :1])
+
+
+def test_extreme_shapes_and_single_row():
+    """Smallest shapes (one sequence, one KV head, one-page table), widest group (8 query heads per KV head),
+    fp32 with head_dim 128 and 32-token pages (the largest register tile), many short sequences."""
+    print("case extreme shapes", flush=True)
+    for dt, D, B, Hk, G, lens in (("f32", 128, 32, 1, 8, [1]), ("bf16", 64, 16, 1, 1, [16]), ("f32", 64, 32, 1, 5, [31]),
+                                  ("bf16", 128, 16, 3, 7, [2] * 70), ("f32", 128, 32, 2, 8, [97, 3000])):
+        extra = 0 if len(lens) == 1 else 1
+        k_pool, v_pool, table, sl = make_paged(950 + D + B + G, lens, Hk, D, B, DTYPES[dt], extra=extra)
+        S, Hq, mb, P = len(lens), Hk * G, table.shape[2], k_pool.shape[0]
+        g = torch.Generator().manual_seed(951)
+        q = torch.randn((S, Hq, D), generator=g).to(DTYPES[dt])
+        desc = pe.make_desc(DTYPES[dt], S, Hk, Hq, D, B, mb, P)
+        kd, vd, td, ld = (x.to(DEV) for x in (k_pool, v_pool, table, sl))
+        # scores
+        got = gpu_scores(k_pool, v_pool, table, sl, Hq)
+        want = oracle.score_blocks(f32(k_pool), f32(v_pool), i32(table), i32(sl))
+        assert np.array_equal(np.isinf(got), np.isinf(want))
+        fin = np.isfinite(want)
+        assert fin.sum() == 0 or _ulp_diff(got[fin], want[fin]).max() <= 1
+        # attention
+        out = torch.empty((S, Hq, D), dtype=DTYPES[dt], device=DEV)
+        ws = pe.alloc_workspace(pe.PE_OP_PAGED_DECODE, desc)
+        pe.pe_paged_decode(desc, q.to(DEV), kd, vd, td, ld, D ** -0.5, out, ws)
+        torch.cuda.synchronize()
+        e2, emax = rel_err(f32(out), oracle.paged_decode(f32(q), f32(k_pool), f32(v_pool), i32(table), i32(sl)))
+        assert e2 <= TOL[dt] and emax <= TOL[dt], (dt, D, B, Hk, G, e2, emax)
