@@ -5,9 +5,9 @@
 // Four kernels on one stream:
 //   1. token_scores:  sweep of the packed K/V prompt; S_i = ||V_i||/||K_i|| in fp64, rounded once to
 //                     fp32, stored per KV head as a contiguous run  scores[hk][token].
-//   2. select:        per row, radix select (4 passes of 8 bits, most significant first) on the fp32 bit
-//                     patterns (scores are >= +0, so they order like unsigned integers) for the E-th
-//                     smallest score T and the number q of tokens equal to T that must go.
+//   2. select:        per row, radix select (digits of 12, 10 and 10 bits, most significant first) on the
+//                     fp32 bit patterns (scores are >= +0, so they order like unsigned integers) for the
+//                     E-th smallest score T and the number q of tokens equal to T that must go.
 //   3. chunk_counts:  per row and chunk of 1024 tokens, how many scores are > T and how many == T.
 //   4. gather:        per row and chunk, an index-ordered scan turns those counts into the destination
 //                     of every kept token; token rows are then copied with 16-byte lane accesses.
@@ -116,12 +116,22 @@ __global__ __launch_bounds__(kThreads) void token_scores_kernel(const T* __restr
 }
 
 // ---- 2. per-row radix select ------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void select_kernel(const float* __restrict__ scores,
-                                                          const int32_t* __restrict__ cu_seqlens,
-                                                          uint32_t* __restrict__ sel, int32_t* __restrict__ seq_lens_out,
-                                                          int32_t* __restrict__ kept_idx_out, int64_t total_tokens,
-                                                          int num_kv_heads, int budget) {
-  __shared__ uint32_t hist[256];
+// One workgroup of 1024 threads per row; three passes over the row's fp32 bit patterns, most significant
+// digit first: 12 bits (sign, exponent, top three mantissa bits: scores of one row cluster in a few
+// exponents, and a narrower first digit would pile every LDS atomic onto three or four bins), then
+// 10 + 10 bits.  After a pass the digit that holds rank k is found with a workgroup-wide scan.
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / kWave;
+constexpr int kSelBins = 4096;
+
+__global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores,
+                                                             const int32_t* __restrict__ cu_seqlens,
+                                                             uint32_t* __restrict__ sel,
+                                                             int32_t* __restrict__ seq_lens_out,
+                                                             int32_t* __restrict__ kept_idx_out, int64_t total_tokens,
+                                                             int num_kv_heads, int budget) {
+  __shared__ uint32_t hist[kSelBins];
+  __shared__ uint32_t wave_tot[kSelWaves];
   __shared__ uint32_t sh_prefix, sh_k;
   const int row = (int)blockIdx.x;
   const int s = row / num_kv_heads, h = row % num_kv_heads;
@@ -131,10 +141,11 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
   const int E = L - keep;
   const uint32_t* bits = reinterpret_cast<const uint32_t*>(scores) + (int64_t)h * total_tokens + t0;
   const int tid = (int)threadIdx.x;
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
 
   if (h == 0 && tid == 0) seq_lens_out[s] = keep;
   if (kept_idx_out != nullptr)
-    for (int i = keep + tid; i < budget; i += kThreads) kept_idx_out[(int64_t)row * budget + i] = -1;
+    for (int i = keep + tid; i < budget; i += kSelThreads) kept_idx_out[(int64_t)row * budget + i] = -1;
 
   if (E == 0) {  // nothing to evict: T = +0.0, q = 0 keeps every token (scores are >= +0)
     if (tid == 0) {
@@ -145,43 +156,47 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
   }
   uint32_t prefix = 0u, mask = 0u;
   uint32_t k = (uint32_t)(E - 1);  // 0-based rank of the threshold element among the remaining ones
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    hist[tid] = 0u;
+#pragma unroll 1
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = pass == 0 ? 20 : pass == 1 ? 10 : 0;
+    const int nbins = pass == 0 ? 4096 : 1024;
+    const int per_thread = nbins / kSelThreads;  // 4 or 1 consecutive bins per thread
+    for (int i = tid; i < nbins; i += kSelThreads) hist[i] = 0u;
     __syncthreads();
-    for (int i = tid; i < L; i += kThreads) {
+    for (int i = tid; i < L; i += kSelThreads) {
       const uint32_t b = bits[i];
-      if ((b & mask) == prefix) atomicAdd(&hist[(b >> shift) & 0xffu], 1u);
+      if ((b & mask) == prefix) atomicAdd(&hist[(b >> shift) & (uint32_t)(nbins - 1)], 1u);
     }
     __syncthreads();
-    if (tid < kWave) {  // one wave: find the digit whose cumulative count passes k
-      uint32_t c[4], tot = 0u;
+    // workgroup-wide exclusive scan of the per-thread bin totals, in bin order
+    uint32_t c[4] = {0u, 0u, 0u, 0u}, tot = 0u;
+    for (int j = 0; j < per_thread; ++j) {
+      c[j] = hist[tid * per_thread + j];
+      tot += c[j];
+    }
+    uint32_t incl = tot;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        c[j] = hist[tid * 4 + j];
-        tot += c[j];
-      }
-      uint32_t incl = tot;  // inclusive scan over the 64 lanes
-#pragma unroll
-      for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t o = (uint32_t)__shfl_up((int)incl, off, kWave);
-        if (tid >= off) incl += o;
-      }
-      uint32_t before = incl - tot;
-      if (k >= before && k < incl) {  // exactly one lane
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (k >= before && k < before + c[j]) {
-            sh_prefix = prefix | ((uint32_t)(tid * 4 + j) << shift);
-            sh_k = k - before;
-          }
-          before += c[j];
+    for (int off = 1; off < kWave; off <<= 1) {
+      const uint32_t o = (uint32_t)__shfl_up((int)incl, off, kWave);
+      if (lane >= off) incl += o;
+    }
+    if (lane == kWave - 1) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t before = incl - tot;
+    for (int w = 0; w < wave; ++w) before += wave_tot[w];
+    if (k >= before && k < before + tot) {  // exactly one thread: rank k falls into one of its bins
+      for (int j = 0; j < per_thread; ++j) {
+        if (k >= before && k < before + c[j]) {
+          sh_prefix = prefix | ((uint32_t)(tid * per_thread + j) << shift);
+          sh_k = k - before;
         }
+        before += c[j];
       }
     }
     __syncthreads();
     prefix = sh_prefix;
     k = sh_k;
-    mask |= 0xffu << shift;
+    mask |= (uint32_t)(nbins - 1) << shift;
     __syncthreads();
   }
   if (tid == 0) {
@@ -365,7 +380,7 @@ hipError_t launch(const PruneArgs& a, hipStream_t stream) {
                        (const T*)a.k_in, (const T*)a.v_in, w.scores, total_rows, a.total_tokens, a.num_kv_heads);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(select_kernel, dim3((unsigned)rows), dim3(kThreads), 0, stream, w.scores, a.cu_seqlens, w.sel,
+  hipLaunchKernelGGL(select_kernel, dim3((unsigned)rows), dim3(kSelThreads), 0, stream, w.scores, a.cu_seqlens, w.sel,
                      a.seq_lens_out, a.kept_idx_out, a.total_tokens, a.num_kv_heads, a.budget);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const int chunks_per_row = (a.max_seqlen + kChunk - 1) / kChunk;
