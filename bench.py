@@ -7,7 +7,8 @@ A step is one decode iteration of ALL layers over the whole batch: on steps wher
 the sequences has just filled at budget, one block-score sweep and one eviction over all layers (layers
 folded into the sequence dimension), then per layer the append of the new token and the paged attention,
 back to back on one stream.  K/V pools, tables and the per-step inputs are resident in HBM before the
-timed region.  Prints ONE JSON line (see the design doc for the fields' derivations).
+timed region.  Prints ONE JSON line: tokens/s of the whole job, the roofline object of the attention kernel
+(algorithmic bytes per launch over its measured launch time, against 8 TB/s) and the CPU oracle's rate.
 """
 import argparse
 import json
@@ -136,7 +137,7 @@ def cpu_baseline(wl, seed, n_seqs, n_layers, steps):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards with no collective; see DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU (rows are independent, the path shards with no collective); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
     import torch

@@ -168,11 +168,12 @@ def test_llama31_8b_subset():
     assert n_ev == 2
 
 
-@pytest.mark.parametrize("B,C", [(16, 4096), (32, 8192)])
-def test_long_context_subset(B, C):
-    """Configuration 5 shape: one 65536-token prompt, budgets 4096 / 8192, page sizes 16 / 32."""
-    print("case loop long", B, C, flush=True)
-    wl = synth.LONG_8B.with_(num_seqs=1, block_size=B, budget=C)
+@pytest.mark.parametrize("B,C,L", [(16, 4096, 65536), (32, 8192, 65536), (32, 8192, 131072), (16, 4096, 131072)])
+def test_long_context_subset(B, C, L):
+    """Configuration 5 shape: one 65536- or 131072-token prompt (the largest), budgets 4096 / 8192, page sizes
+    16 / 32: prefill select over a row far larger than LDS, 8 attention splits per row."""
+    print("case loop long", B, C, L, flush=True)
+    wl = synth.LONG_8B.with_(num_seqs=1, block_size=B, budget=C, context=(L,))
     n_ev, worst = run_loop(wl, B + 2, check_pool=False)
     assert n_ev == 2
     print("long worst attention error", worst, flush=True)
