@@ -485,14 +485,19 @@ __global__ __launch_bounds__(D) void paged_decode_reduce_kernel(const float* __r
   const int d = (int)threadIdx.x;
   const float* base = partials + (((int64_t)row * splits) * g_real + h) * (D + 2);
   const int64_t stride = (int64_t)g_real * (D + 2);
-  float mm = kNegInf;
-  for (int sp = 0; sp < splits; ++sp) mm = fmaxf(mm, base[sp * stride + D]);
-  const float ms = mm == kNegInf ? 0.f : mm;
-  float o = 0.f, l = 0.f;
+  // one pass, online: all loads are independent of the running state, so they overlap
+  float mm = kNegInf, o = 0.f, l = 0.f;
+#pragma unroll 4
   for (int sp = 0; sp < splits; ++sp) {
-    const float w = __builtin_amdgcn_exp2f(base[sp * stride + D] - ms);
-    l = fmaf(base[sp * stride + D + 1], w, l);
-    o = fmaf(base[sp * stride + d], w, o);
+    const float m_sp = base[sp * stride + D];
+    const float l_sp = base[sp * stride + D + 1];
+    const float a_sp = base[sp * stride + d];
+    const float m_new = fmaxf(mm, m_sp);
+    const float ms = m_new == kNegInf ? 0.f : m_new;
+    const float w_old = __builtin_amdgcn_exp2f(mm - ms), w_new = __builtin_amdgcn_exp2f(m_sp - ms);
+    l = fmaf(l, w_old, l_sp * w_new);
+    o = fmaf(o, w_old, a_sp * w_new);
+    mm = m_new;
   }
   const float r = l > 0.f ? o / l : 0.f;
   const int64_t off = (int64_t)sh * D + d;

@@ -89,24 +89,18 @@ __device__ __forceinline__ double lane_xor_f64(double v) {
   return __hiloint2double(hi, lo);
 }
 
-// Broadcast of position J (0..3) of every aligned group of four lanes.
-template <int J>
-__device__ __forceinline__ float quad_bcast_f32(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), J * 0x55, 0xf, 0xf, true));
-}
-
 // Value of lane ((lane & ~(W-1)) | J): broadcast of position J of every aligned group of W lanes.
 template <int W, int J>
 __device__ __forceinline__ float group_bcast_f32(float v) {
   static_assert(W == 1 || W == 2 || W == 4 || W == 8, "group width");
+  static_assert(J >= 0 && J < W, "position inside the group");
   if constexpr (W == 1) {
     return v;
-  } else if constexpr (W <= 4) {
-    // W == 2: positions inside the quad are (lane & 2) | J
-    constexpr int p0 = (W == 2) ? J : J, p1 = (W == 2) ? J : J, p2 = (W == 2) ? (2 | J) : J,
-                  p3 = (W == 2) ? (2 | J) : J;
-    return __int_as_float(
-        __builtin_amdgcn_update_dpp(0, __float_as_int(v), p0 | (p1 << 2) | (p2 << 4) | (p3 << 6), 0xf, 0xf, true));
+  } else if constexpr (W == 2) {  // quad positions 0,1 read position J; positions 2,3 read position 2+J
+    constexpr int ctrl = J | (J << 2) | ((2 | J) << 4) | ((2 | J) << 6);
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, 0xf, 0xf, true));
+  } else if constexpr (W == 4) {  // quad_perm [J,J,J,J]
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), J * 0x55, 0xf, 0xf, true));
   } else {
     // ds_swizzle bit-mask mode: lane' = ((lane & and) | or) ^ xor inside each half-wave
     return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), (J << 5) | 0x18));

@@ -179,13 +179,18 @@ def test_long_context_subset(B, C, L):
     print("long worst attention error", worst, flush=True)
 
 
-def test_headline_full_size_one_layer_and_determinism():
-    """The headline shape at full size (32 sequences x 8 KV heads x 2048 tokens, bf16, shuffled pool), one
-    layer of the layered driver the benchmark uses, in the benchmark's launch configuration: every score,
-    every eviction decision, the whole table and every attention output against the oracle, for a trigger
-    step and a plain step; then the same step again from the same state must give identical bytes."""
-    print("case headline full size", flush=True)
-    wl = synth.LLAMA31_8B
+FULL_SIZE = [synth.LLAMA31_8B, synth.LLAMA32_1B, synth.LLAMA32_1B.with_(budget=2048), synth.LLAMA32_3B, synth.LONG_8B,
+             synth.LONG_8B.with_(block_size=32, budget=8192)]
+
+
+@pytest.mark.parametrize("wl", FULL_SIZE, ids=lambda w: "%s_C%d_B%d" % (w.name, w.budget, w.block_size))
+def test_full_size_one_layer_and_determinism(wl):
+    """Every benchmark shape at its full batch and budget (the headline one: 32 sequences x 8 KV heads x 2048
+    tokens, bf16, shuffled pool), one layer of the layered driver the benchmark uses, in the benchmark's launch
+    configuration (same split count, fused append): every score, every eviction decision, the whole table and
+    every attention output against the oracle, for a trigger step and a plain step; then the same launch
+    again from the same state must give identical bytes."""
+    print("case full size", wl.name, wl.budget, wl.block_size, flush=True)
     layers = 2                                   # two layers share the pool; layer 1 is compared
     S, Hk, Hq, D, B, C = wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim, wl.block_size, wl.budget
     lens = [C] * S                               # the state right after the prune: every row at budget
@@ -216,6 +221,7 @@ def test_headline_full_size_one_layer_and_determinism():
         want, oscores, oev, ofr = oracle_step(ocache, f32(nk[l]), f32(nv[l]), f32(q[l]))
         trig = eng.decode_step(nk.to(DEV), nv.to(DEV), q.to(DEV), out)
         torch.cuda.synchronize()
+        gl = eng.per_layer[l]
         assert trig == (step == 0)
         assert np.array_equal(gl.block_table.cpu().numpy(), ocache.block_table)
         assert np.array_equal(gl.seq_lens.cpu().numpy(), ocache.seq_lens)
@@ -226,9 +232,9 @@ def test_headline_full_size_one_layer_and_determinism():
             assert np.array_equal(np.isinf(gs), np.isinf(oscores))
             ulp = _ulp(gs[fin], oscores[fin])
             assert ulp.max() <= 1
-            print("headline: %d scores, %d not bit-equal" % (fin.sum(), int((ulp != 0).sum())), flush=True)
+            print("full size: %d scores, %d not bit-equal" % (fin.sum(), int((ulp != 0).sum())), flush=True)
         e2, emax = rel_err(f32(out[l]), want)
-        print("headline step %d attention error %.3g %.3g" % (step, e2, emax), flush=True)
+        print("full size step %d attention error %.3g %.3g" % (step, e2, emax), flush=True)
         assert e2 <= 2e-2 and emax <= 2e-2
     # determinism: the same attention launch twice gives identical bytes; the plain attention call on the
     # post-append state agrees with what the fused append + attention launch produced (same sum, other order)
