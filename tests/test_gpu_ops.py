@@ -420,3 +420,36 @@ def test_extreme_shapes_and_single_row():
         torch.cuda.synchronize()
         e2, emax = rel_err(f32(out), oracle.paged_decode(f32(q), f32(k_pool), f32(v_pool), i32(table), i32(sl)))
         assert e2 <= TOL[dt] and emax <= TOL[dt], (dt, D, B, Hk, G, e2, emax)
+
+
+def test_calls_run_on_the_callers_stream():
+    """Every call enqueues on the stream it is given: work issued on a side stream, behind a long-running
+    producer on that stream, must see the producer's result without any extra synchronisation."""
+    print("case side stream", flush=True)
+    Hk, G, D, B = 2, 4, 128, 16
+    lens = [300, 77]
+    k_pool, v_pool, table, sl = make_paged(990, lens, Hk, D, B, torch.bfloat16)
+    S, Hq, mb, P = 2, Hk * G, table.shape[2], k_pool.shape[0]
+    g = torch.Generator().manual_seed(991)
+    q = torch.randn((S, Hq, D), generator=g).to(torch.bfloat16)
+    want = oracle.paged_decode(f32(q), f32(k_pool), f32(v_pool), i32(table), i32(sl))
+    desc = pe.make_desc(torch.bfloat16, S, Hk, Hq, D, B, mb, P)
+    kd, vd, td, ld = (x.to(DEV) for x in (k_pool, v_pool, table, sl))
+    ws = pe.alloc_workspace(pe.PE_OP_PAGED_DECODE, desc)
+    side = torch.cuda.Stream()
+    qd = torch.zeros((S, Hq, D), dtype=torch.bfloat16, device=DEV)
+    out = torch.empty_like(qd)
+    scores = torch.empty((S, Hk, mb), dtype=torch.float32, device=DEV)
+    big = torch.empty(1 << 28, dtype=torch.uint8, device=DEV)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for _ in range(8):
+            big.fill_(1)                      # keeps the side stream busy for a while
+        qd.copy_(q.to(DEV, non_blocking=True))   # the query only becomes valid on this stream, after the fills
+        pe.pe_paged_decode(desc, qd, kd, vd, td, ld, D ** -0.5, out, ws)
+        pe.pe_score_blocks(desc, kd, vd, td, ld, scores)
+    side.synchronize()
+    e2, emax = rel_err(f32(out), want)
+    assert e2 <= 2e-2 and emax <= 2e-2
+    assert np.array_equal(np.isinf(scores.cpu().numpy()),
+                          np.isinf(oracle.score_blocks(f32(k_pool), f32(v_pool), i32(table), i32(sl))))
