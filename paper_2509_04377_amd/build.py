@@ -37,7 +37,22 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     tmp = LIB + ".tmp.%d" % os.getpid()
     subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs, check=True)
     os.replace(tmp, LIB)
+    build_c_smoke()
     return LIB
+
+
+C_SMOKE_SRC = os.path.join(os.path.dirname(HERE), "tests", "c_abi", "pe_c_smoke.c")
+C_SMOKE_BIN = os.path.join(HERE, "pe_c_smoke")
+
+
+def build_c_smoke() -> str:
+    """A plain-C program that drives libpe through the C ABI (used by a GPU test); built with gcc."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"), "-o",
+           C_SMOKE_BIN, C_SMOKE_SRC, "-L", HERE, "-lpe", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    subprocess.run(cmd, check=True)
+    return C_SMOKE_BIN
 
 
 if __name__ == "__main__":

@@ -1,0 +1,128 @@
+/*
+ * Plain-C caller of libpe: no Python, no torch, only the HIP runtime for device memory.
+ * Closed-form inputs, checked on the host:
+ *   - V = K in every page            -> every block score is exactly 1.0f;
+ *   - page scores 3, 1, 2, 1 given   -> eviction drops logical page 1 (tie -> lowest index);
+ *   - q = 0                          -> attention output = mean of the cached V rows.
+ * Exit status 0 on success.
+ */
+#include <hip/hip_runtime_api.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "../../include/pe.h"
+
+#define CHECK_HIP(x)                                                       \
+  do {                                                                     \
+    hipError_t e_ = (x);                                                   \
+    if (e_ != hipSuccess) {                                                \
+      fprintf(stderr, "HIP error %d at line %d\n", (int)e_, __LINE__);     \
+      return 2;                                                            \
+    }                                                                      \
+  } while (0)
+#define CHECK_PE(x)                                                                     \
+  do {                                                                                  \
+    int s_ = (x);                                                                       \
+    if (s_ != PE_OK) {                                                                  \
+      fprintf(stderr, "pe error %d (%s) at line %d\n", s_, pe_status_string(s_), __LINE__); \
+      return 3;                                                                         \
+    }                                                                                   \
+  } while (0)
+
+enum { S = 1, HK = 2, HQ = 4, D = 64, B = 16, MAXB = 5, P = 12, NPAGES = 4 };
+
+int main(void) {
+  pe_cache_desc desc = {PE_F32, S, HK, HQ, D, B, MAXB, P};
+  const size_t pool_elems = (size_t)P * B * D;
+  float* h_k = (float*)malloc(pool_elems * sizeof(float));
+  int32_t h_table[S * HK * MAXB];
+  int32_t h_len[S] = {NPAGES * B};
+  for (size_t i = 0; i < pool_elems; ++i) h_k[i] = (float)((i * 2654435761u) % 17) - 8.0f + 0.5f;  /* never a zero row */
+  for (int h = 0; h < HK; ++h)
+    for (int j = 0; j < MAXB; ++j) h_table[h * MAXB + j] = j < NPAGES ? (h * NPAGES + j + 1) % P : -1;
+
+  float *d_k, *d_v, *d_scores, *d_q, *d_out;
+  int32_t *d_table, *d_len, *d_ev, *d_fr;
+  CHECK_HIP(hipMalloc((void**)&d_k, pool_elems * sizeof(float)));
+  CHECK_HIP(hipMalloc((void**)&d_v, pool_elems * sizeof(float)));
+  CHECK_HIP(hipMalloc((void**)&d_scores, sizeof(float) * S * HK * MAXB));
+  CHECK_HIP(hipMalloc((void**)&d_q, sizeof(float) * S * HQ * D));
+  CHECK_HIP(hipMalloc((void**)&d_out, sizeof(float) * S * HQ * D));
+  CHECK_HIP(hipMalloc((void**)&d_table, sizeof(h_table)));
+  CHECK_HIP(hipMalloc((void**)&d_len, sizeof(h_len)));
+  CHECK_HIP(hipMalloc((void**)&d_ev, sizeof(int32_t) * S * HK));
+  CHECK_HIP(hipMalloc((void**)&d_fr, sizeof(int32_t) * S * HK));
+  CHECK_HIP(hipMemcpy(d_k, h_k, pool_elems * sizeof(float), hipMemcpyHostToDevice));
+  CHECK_HIP(hipMemcpy(d_v, h_k, pool_elems * sizeof(float), hipMemcpyHostToDevice)); /* V = K */
+  CHECK_HIP(hipMemcpy(d_table, h_table, sizeof(h_table), hipMemcpyHostToDevice));
+  CHECK_HIP(hipMemcpy(d_len, h_len, sizeof(h_len), hipMemcpyHostToDevice));
+  CHECK_HIP(hipMemset(d_q, 0, sizeof(float) * S * HQ * D));
+  hipStream_t stream;
+  CHECK_HIP(hipStreamCreate(&stream));
+
+  /* (1) block scores */
+  CHECK_PE(pe_score_blocks(&desc, d_k, d_v, d_table, d_len, d_scores, NULL, 0, stream));
+  float h_scores[S * HK * MAXB];
+  CHECK_HIP(hipStreamSynchronize(stream));
+  CHECK_HIP(hipMemcpy(h_scores, d_scores, sizeof(h_scores), hipMemcpyDeviceToHost));
+  for (int h = 0; h < HK; ++h)
+    for (int j = 0; j < MAXB; ++j) {
+      const float v = h_scores[h * MAXB + j];
+      if (j < NPAGES ? v != 1.0f : !(isinf(v) && v > 0)) {
+        fprintf(stderr, "score[%d][%d] = %g\n", h, j, v);
+        return 1;
+      }
+    }
+
+  /* (4) attention with q = 0: the mean of the cached V rows (here V = K) */
+  size_t ws_bytes = pe_workspace_bytes(PE_OP_PAGED_DECODE, &desc, 0);
+  void* d_ws = NULL;
+  if (ws_bytes) CHECK_HIP(hipMalloc(&d_ws, ws_bytes));
+  CHECK_PE(pe_paged_decode(&desc, d_q, d_k, d_v, d_table, d_len, 0.125f, d_out, d_ws, ws_bytes, stream));
+  float h_out[S * HQ * D];
+  CHECK_HIP(hipStreamSynchronize(stream));
+  CHECK_HIP(hipMemcpy(h_out, d_out, sizeof(h_out), hipMemcpyDeviceToHost));
+  for (int hq = 0; hq < HQ; ++hq) {
+    const int h = hq / (HQ / HK);
+    for (int d = 0; d < D; ++d) {
+      double mean = 0.0;
+      for (int t = 0; t < NPAGES * B; ++t)
+        mean += h_k[((size_t)h_table[h * MAXB + t / B] * B + t % B) * D + d];
+      mean /= NPAGES * B;
+      if (fabs(h_out[hq * D + d] - mean) > 1e-5 * (1.0 + fabs(mean))) {
+        fprintf(stderr, "out[%d][%d] = %g, want %g\n", hq, d, h_out[hq * D + d], mean);
+        return 1;
+      }
+    }
+  }
+
+  /* (3) eviction from given scores: 3 1 2 1 -> logical page 1 */
+  const float given[MAXB] = {3.f, 1.f, 2.f, 1.f, INFINITY};
+  for (int h = 0; h < HK; ++h) memcpy(h_scores + h * MAXB, given, sizeof(given));
+  CHECK_HIP(hipMemcpy(d_scores, h_scores, sizeof(h_scores), hipMemcpyHostToDevice));
+  CHECK_PE(pe_evict_blocks(&desc, d_scores, d_table, d_len, NPAGES * B, d_ev, d_fr, stream));
+  int32_t h_ev[HK], h_fr[HK], h_table2[S * HK * MAXB], h_len2[S];
+  CHECK_HIP(hipStreamSynchronize(stream));
+  CHECK_HIP(hipMemcpy(h_ev, d_ev, sizeof(h_ev), hipMemcpyDeviceToHost));
+  CHECK_HIP(hipMemcpy(h_fr, d_fr, sizeof(h_fr), hipMemcpyDeviceToHost));
+  CHECK_HIP(hipMemcpy(h_table2, d_table, sizeof(h_table2), hipMemcpyDeviceToHost));
+  CHECK_HIP(hipMemcpy(h_len2, d_len, sizeof(h_len2), hipMemcpyDeviceToHost));
+  for (int h = 0; h < HK; ++h) {
+    const int32_t* o = h_table + h * MAXB;
+    const int32_t* n = h_table2 + h * MAXB;
+    if (h_ev[h] != 1 || h_fr[h] != o[1] || n[0] != o[0] || n[1] != o[2] || n[2] != o[3] || n[3] != -1) {
+      fprintf(stderr, "eviction of head %d wrong\n", h);
+      return 1;
+    }
+  }
+  if (h_len2[0] != (NPAGES - 1) * B) return 1;
+
+  /* host-detectable misuse is refused without a launch */
+  if (pe_evict_blocks(&desc, d_scores, d_table, d_len, 24, d_ev, d_fr, stream) != PE_ERR_INVALID_ARG) return 1;
+  if (pe_score_blocks(&desc, NULL, d_v, d_table, d_len, d_scores, NULL, 0, stream) != PE_ERR_INVALID_ARG) return 1;
+  printf("pe_c_smoke ok (libpe version %d)\n", pe_version());
+  return 0;
+}
