@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--cached-scores", action="store_true",
                     help="keep page scores across steps and score only newly filled pages (not the paper's stated "
                          "procedure; the score sweep then drops out of the byte count too)")
+    ap.add_argument("--fused-evict", action="store_true",
+                    help="score + evict of a trigger step in one launch (pe_score_evict)")
     ap.add_argument("--graph", action="store_true", help="replay each step from captured HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=16)
@@ -166,6 +168,7 @@ def main():
     eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev)
     eng.fused = not args.unfused
     eng.folded.cached_scores = args.cached_scores
+    eng.folded.fused_evict = args.fused_evict
     L, S, Hk, Hq, D = wl.layers, wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim
     elem = 2 if wl.dtype == "bf16" else 4
 
@@ -248,7 +251,7 @@ def main():
         "config": {"workload": "%s: %d layers, %d seqs x %d KV heads (%d q heads), head_dim %d, page %d, context %s -> "
                                "budget %d" % (wl.name, L, S, Hk, Hq, D, wl.block_size, "/".join(map(str, wl.context)),
                                               wl.budget),
-                   "decode_splits": pe.pe_get_option(pe.PE_OPT_DECODE_SPLITS), "fused_append": eng.fused, "cached_scores": args.cached_scores, "hip_graph": args.graph,
+                   "decode_splits": pe.pe_get_option(pe.PE_OPT_DECODE_SPLITS), "fused_append": eng.fused, "cached_scores": args.cached_scores, "fused_evict": args.fused_evict, "hip_graph": args.graph,
                    "trigger_steps": n_trigger},
         "step_ms": {"p50": step_ms[len(step_ms) // 2], "p99": step_ms[min(len(step_ms) - 1, int(len(step_ms) * 0.99))],
                     "max": step_ms[-1]},

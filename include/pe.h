@@ -160,6 +160,18 @@ int pe_evict_blocks_cached(const pe_cache_desc* desc, float* scores_inout, int32
                            void* stream);
 
 /*
+ * (1)+(3) in one launch -- the whole "if L % B == 0" branch of Alg. 3.  Equal in effect to pe_score_blocks
+ * followed by pe_evict_blocks, except that only triggering sequences are scored: their rows' pages are swept
+ * once, the running minimum is kept (ties: lowest index), the table row is compacted and seq_lens[s] -= B.
+ * scores_out: NULL, or [S][Hk][max_blocks] fp32; rows of triggering sequences receive the scores the decision
+ * was taken on (before compaction; entries j >= seq_lens[s]/B are +INF), rows of other sequences are left
+ * untouched.  evicted_logical_out / freed_phys_out as in (3).
+ */
+int pe_score_evict(const pe_cache_desc* desc, const void* k_pool, const void* v_pool, int32_t* block_table,
+                   int32_t* seq_lens, int32_t budget_tokens, float* scores_out, int32_t* evicted_logical_out,
+                   int32_t* freed_phys_out, void* stream);
+
+/*
  * Eviction variants on the same table machinery (not the paper's main method).  Sec. 5.2 / App. A describe
  * StreamingLLM (a few first tokens kept as attention sinks plus a window of the most recent ones); Sec. 2.4
  * leaves open whether heads decide separately.  opts->policy: PE_POLICY_LOWEST_SCORE (as (3)) or

@@ -24,7 +24,7 @@ PE_OPT_DECODE_LOADS = 4
 
 EXPORTS = ["pe_workspace_bytes", "pe_status_string", "pe_version", "pe_set_option", "pe_get_option",
            "pe_score_blocks", "pe_prefill_prune", "pe_evict_blocks", "pe_paged_decode", "pe_append_kv",
-           "pe_append_paged_decode", "pe_score_recent_blocks", "pe_evict_blocks_cached", "pe_evict_blocks_ex"]
+           "pe_append_paged_decode", "pe_score_recent_blocks", "pe_evict_blocks_cached", "pe_evict_blocks_ex", "pe_score_evict"]
 
 
 class pe_cache_desc(ctypes.Structure):
@@ -76,6 +76,8 @@ def lib():
         L.pe_prefill_prune.argtypes = [dp, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.pe_evict_blocks.restype = ctypes.c_int
         L.pe_evict_blocks.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp]
+        L.pe_score_evict.restype = ctypes.c_int
+        L.pe_score_evict.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.pe_paged_decode.restype = ctypes.c_int
         L.pe_paged_decode.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
         L.pe_append_kv.restype = ctypes.c_int
@@ -204,6 +206,17 @@ def pe_evict_blocks(desc, scores, block_table, seq_lens, budget_tokens, evicted_
                                  _ptr(freed_phys_out, "freed_phys_out", torch.int32), _stream()), "pe_evict_blocks")
 
 
+def pe_score_evict(desc, k_pool, v_pool, block_table, seq_lens, budget_tokens, scores_out, evicted_logical_out,
+                   freed_phys_out):
+    if _HostOnly.active:
+        return
+    _check(lib().pe_score_evict(ctypes.byref(desc), _ptr(k_pool, "k_pool"), _ptr(v_pool, "v_pool"),
+                                _ptr(block_table, "block_table", torch.int32), _ptr(seq_lens, "seq_lens", torch.int32),
+                                int(budget_tokens), _ptr(scores_out, "scores_out", torch.float32, optional=True),
+                                _ptr(evicted_logical_out, "evicted_logical_out", torch.int32),
+                                _ptr(freed_phys_out, "freed_phys_out", torch.int32), _stream()), "pe_score_evict")
+
+
 def pe_score_recent_blocks(desc, k_pool, v_pool, block_table, seq_lens, recent, scores_inout):
     if _HostOnly.active:
         return
@@ -295,6 +308,7 @@ class PagedCache:
     cached_scores: bool = False    # keep `scores` alive across steps and score only newly filled pages
     host_scored: list = None       # per sequence: full pages whose score is in `scores` (host bookkeeping)
     evict_opts: pe_evict_opts = None  # eviction variant (policy, protected pages, shared heads); None = Alg. 3
+    fused_evict: bool = False  # score + evict of a trigger step in one launch (pe_score_evict)
 
     @staticmethod
     def create(dtype, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, layout, budget, device="cuda",
@@ -374,6 +388,10 @@ class PagedCache:
                 self.score_blocks()
             pe_evict_blocks_ex(self.desc, opts, self.scores if o.policy != PE_POLICY_OLDEST else None,
                                self.block_table, self.seq_lens, self.budget, self.evicted_logical, self.freed_phys)
+            return
+        if self.fused_evict and not self.cached_scores:
+            pe_score_evict(self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, self.budget, None,
+                           self.evicted_logical, self.freed_phys)
             return
         if not self.cached_scores:
             self.score_blocks()

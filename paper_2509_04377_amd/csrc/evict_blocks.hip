@@ -10,6 +10,7 @@
 // left by one, 64 entries per pass.  seq_lens[s] is read by every wave before the barrier and
 // written once after it.
 #include "pe_device.h"
+#include "pe_evict_common.h"
 #include "pe_launch.h"
 
 namespace pe {
@@ -102,28 +103,8 @@ __global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* sco
       min_step<32>(best, best_j);
       jstar = __builtin_amdgcn_readfirstlane(best_j);
     }
-    const int freed = bt[jstar];
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_s_waitcnt(0);  // the evicted entry has been read before any store below is issued
-    // stable left shift of entries jstar+1 .. n-1; each pass loads its 64 sources before it stores,
-    // and a pass only stores to positions that later passes do not read.
     float* sc_mut = scores_mut != nullptr ? scores_mut + row * max_blocks : nullptr;
-    for (int base = (jstar / kWave) * kWave; base < n; base += kWave) {
-      const int j = base + lane;
-      const bool move = j >= jstar && j < n;
-      int32_t v = -1;
-      float sv = __builtin_inff();
-      if (move && j + 1 < n) {
-        v = bt[j + 1];
-        if (sc_mut != nullptr) sv = sc_mut[j + 1];
-      }
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      __builtin_amdgcn_s_waitcnt(0);  // all 64 sources are in registers before the stores are issued
-      if (move) {
-        bt[j] = v;
-        if (sc_mut != nullptr) sc_mut[j] = sv;
-      }
-    }
+    const int freed = compact_row(bt, sc_mut, jstar, n, lane);
     if (lane == 0) {
       evicted_logical[row] = jstar;
       freed_phys[row] = freed;

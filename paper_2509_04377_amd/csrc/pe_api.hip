@@ -197,6 +197,33 @@ int pe_evict_blocks_ex(const pe_cache_desc* desc, const pe_evict_opts* opts, flo
                            evicted_logical_out, freed_phys_out, stream, opts);
 }
 
+int pe_score_evict(const pe_cache_desc* desc, const void* k_pool, const void* v_pool, int32_t* block_table,
+                   int32_t* seq_lens, int32_t budget_tokens, float* scores_out, int32_t* evicted_logical_out,
+                   int32_t* freed_phys_out, void* stream) {
+  const int st = check_desc(desc);
+  if (st != PE_OK) return st;
+  if (!k_pool || !v_pool || !block_table || !seq_lens || !evicted_logical_out || !freed_phys_out)
+    return PE_ERR_INVALID_ARG;
+  if (!aligned(k_pool, 16) || !aligned(v_pool, 16)) return PE_ERR_INVALID_ARG;
+  if (budget_tokens <= 0 || budget_tokens % desc->block_size != 0) return PE_ERR_INVALID_ARG;
+  pe::ScoreEvictArgs a;
+  a.k_pool = k_pool;
+  a.v_pool = v_pool;
+  a.block_table = block_table;
+  a.seq_lens = seq_lens;
+  a.scores_out = scores_out;
+  a.evicted_logical = evicted_logical_out;
+  a.freed_phys = freed_phys_out;
+  a.num_seqs = desc->num_seqs;
+  a.num_kv_heads = desc->num_kv_heads;
+  a.head_dim = desc->head_dim;
+  a.block_size = desc->block_size;
+  a.max_blocks = desc->max_blocks;
+  a.budget = budget_tokens;
+  a.is_bf16 = desc->dtype == PE_BF16;
+  return pe::launch_score_evict(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
+}
+
 int pe_evict_blocks(const pe_cache_desc* desc, const float* scores, int32_t* block_table, int32_t* seq_lens,
                     int32_t budget_tokens, int32_t* evicted_logical_out, int32_t* freed_phys_out, void* stream) {
   return evict_blocks_impl(desc, scores, nullptr, block_table, seq_lens, budget_tokens, evicted_logical_out,

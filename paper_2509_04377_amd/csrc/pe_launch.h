@@ -20,6 +20,19 @@ struct ScoreArgs {
 };
 hipError_t launch_score_blocks(const ScoreArgs& a, hipStream_t stream);
 
+struct ScoreEvictArgs {
+  const void* k_pool;
+  const void* v_pool;
+  int32_t* block_table;
+  int32_t* seq_lens;
+  float* scores_out;  // may be null
+  int32_t* evicted_logical;
+  int32_t* freed_phys;
+  int num_seqs, num_kv_heads, head_dim, block_size, max_blocks, budget;
+  bool is_bf16;
+};
+hipError_t launch_score_evict(const ScoreEvictArgs& a, hipStream_t stream);
+
 struct EvictArgs {
   const float* scores;
   float* scores_mut = nullptr;  // when set (== scores): delete the evicted entry from the score row as well

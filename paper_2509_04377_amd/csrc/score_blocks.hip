@@ -8,6 +8,7 @@
 // keeps the score array alive may ask for the most recently filled pages only (`recent` > 0): the
 // kernel then visits pages nfull - recent .. nfull - 1 of every row and leaves the other entries alone.
 #include "pe_device.h"
+#include "pe_evict_common.h"
 #include "pe_launch.h"
 #include "pe_norms.h"
 
@@ -19,6 +20,52 @@ constexpr int kWaves = kThreads / kWave;
 constexpr int kPagesPerWave = 4;
 constexpr int kPagesPerGroup = kWaves * kPagesPerWave;
 
+// One page scored by one wave.
+template <typename T, int D, int B>
+struct PageScore {
+  using G = RowGeom<T, D>;
+  static constexpr int LPR = G::kLanesPerRow;
+  static constexpr int TPL = G::kTokensPerLoad;
+  static constexpr int NL = B / TPL;  // wave-loads per page
+  static constexpr int NV = 2 * NL;   // per-lane partial sums: (K, V) x NL token rows
+  static_assert(NV <= LPR, "reduce-scatter needs at least as many lanes per row as values");
+  static constexpr int kVecPerPage = B * D / G::kPerVec;
+
+  static __device__ __forceinline__ void issue(uint4 (&kb)[NL], uint4 (&vb)[NL], const T* k_pool, const T* v_pool,
+                                               int phys, int lane) {
+    const int64_t base = (int64_t)phys * kVecPerPage + lane;
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      kb[i] = load_vec_stream(k_pool, base + i * kWave);
+      vb[i] = load_vec_stream(v_pool, base + i * kWave);
+    }
+  }
+
+  // The page's score (the same value in every lane): fp64 throughout, one rounding to fp32.
+  static __device__ __forceinline__ float finish(const uint4 (&kb)[NL], const uint4 (&vb)[NL], int lane) {
+    // value index = kv * NL + i  (kv: 0 = K, 1 = V; i = wave-load = token row i*TPL + lane/LPR)
+    double part[NV];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      part[i] = sumsq_vec<T>(kb[i], 0.0);
+      part[NL + i] = sumsq_vec<T>(vb[i], 0.0);
+    }
+    const double ratio = token_ratio_from_partials<NL, LPR>(part, lane);
+    // page mean, summed in slot order t = 0 .. B-1; token t = i*TPL + g sits on lane g*LPR + 2*bitrev(i)
+    double sum = 0.0;
+#pragma unroll
+    for (int t = 0; t < B; ++t) {
+      constexpr int kBits = ilog2(NL);
+      const int i = t / TPL, g = t % TPL;
+      const int src = g * LPR + 2 * bit_reverse<kBits>(i);
+      const int lo = __builtin_amdgcn_readlane(__double2loint(ratio), src);
+      const int hi = __builtin_amdgcn_readlane(__double2hiint(ratio), src);
+      sum += __hiloint2double(hi, lo);
+    }
+    return (float)(sum / (double)B);
+  }
+};
+
 template <typename T, int D, int B>
 __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restrict__ k_pool,
                                                                 const T* __restrict__ v_pool,
@@ -26,13 +73,8 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
                                                                 const int32_t* __restrict__ seq_lens,
                                                                 float* __restrict__ scores, int num_kv_heads,
                                                                 int max_blocks, int groups_per_row, int recent) {
-  using G = RowGeom<T, D>;
-  constexpr int LPR = G::kLanesPerRow;
-  constexpr int TPL = G::kTokensPerLoad;
-  constexpr int NL = B / TPL;  // wave-loads per page
-  constexpr int NV = 2 * NL;   // per-lane partial sums: (K, V) x NL token rows
-  static_assert(NV <= LPR, "reduce-scatter needs at least as many lanes per row as values");
-  constexpr int kVecPerPage = B * D / G::kPerVec;
+  using PS = PageScore<T, D, B>;
+  constexpr int NL = PS::NL;
 
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
@@ -49,49 +91,89 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
   const int j0 = j_first + grp * kPagesPerGroup + wave;
 
   uint4 kb[2][NL], vb[2][NL];
-  auto issue = [&](int buf, int j) {
-    if (j < nfull) {
-      const int64_t base = (int64_t)bt[j] * kVecPerPage + lane;
-#pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        kb[buf][i] = load_vec_stream(k_pool, base + i * kWave);
-        vb[buf][i] = load_vec_stream(v_pool, base + i * kWave);
-      }
-    }
-  };
-
-  issue(0, j0);
+  if (j0 < nfull) PS::issue(kb[0], vb[0], k_pool, v_pool, bt[j0], lane);
 #pragma unroll
   for (int it = 0; it < kPagesPerWave; ++it) {
     const int j = j0 + it * kWaves;
-    if (it + 1 < kPagesPerWave) issue((it + 1) & 1, j + kWaves);
+    if (it + 1 < kPagesPerWave && j + kWaves < nfull)
+      PS::issue(kb[(it + 1) & 1], vb[(it + 1) & 1], k_pool, v_pool, bt[j + kWaves], lane);
     if (j >= j_end) break;
     if (j >= nfull) {
       if (lane == 0) out[j] = __builtin_inff();
       continue;
     }
-    const int buf = it & 1;
-    // value index = kv * NL + i  (kv: 0 = K, 1 = V; i = wave-load = token row i*TPL + lane/LPR)
-    double part[NV];
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      part[i] = sumsq_vec<T>(kb[buf][i], 0.0);
-      part[NL + i] = sumsq_vec<T>(vb[buf][i], 0.0);
-    }
-    const double ratio = token_ratio_from_partials<NL, LPR>(part, lane);
-    // page mean, summed in slot order t = 0 .. B-1; token t = i*TPL + g sits on lane g*LPR + 2*bitrev(i)
-    double sum = 0.0;
-#pragma unroll
-    for (int t = 0; t < B; ++t) {
-      constexpr int kBits = ilog2(NL);
-      const int i = t / TPL, g = t % TPL;
-      const int src = g * LPR + 2 * bit_reverse<kBits>(i);
-      const int lo = __builtin_amdgcn_readlane(__double2loint(ratio), src);
-      const int hi = __builtin_amdgcn_readlane(__double2hiint(ratio), src);
-      sum += __hiloint2double(hi, lo);
-    }
-    if (lane == 0) out[j] = (float)(sum / (double)B);
+    const float sc = PS::finish(kb[it & 1], vb[it & 1], lane);
+    if (lane == 0) out[j] = sc;
   }
+}
+
+// Score and evict in one launch (Alg. 3, the whole "L % B == 0" branch): one workgroup per sequence, one wave
+// per row at a time.  The wave sweeps the row's pages in logical order with a two-deep register pipeline,
+// keeps the running minimum (a strictly lower score replaces it, so ties stay with the lowest index), then
+// compacts the table row.  Scores are also written out when the caller wants them.
+template <typename T, int D, int B>
+__global__ __launch_bounds__(kThreads) void score_evict_kernel(const T* __restrict__ k_pool,
+                                                               const T* __restrict__ v_pool,
+                                                               int32_t* __restrict__ block_table,
+                                                               int32_t* __restrict__ seq_lens,
+                                                               float* __restrict__ scores_out,
+                                                               int32_t* __restrict__ evicted_logical,
+                                                               int32_t* __restrict__ freed_phys, int num_kv_heads,
+                                                               int max_blocks, int budget) {
+  using PS = PageScore<T, D, B>;
+  constexpr int NL = PS::NL;
+  const int s = (int)blockIdx.x;
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+  const int len = seq_lens[s];
+  const int n = len / B;
+  const bool trigger = len > 0 && (len % B) == 0 && len >= budget && n <= max_blocks;
+
+  for (int h = wave; h < num_kv_heads; h += kWaves) {
+    const int64_t row = (int64_t)s * num_kv_heads + h;
+    if (!trigger) {
+      if (lane == 0) {
+        evicted_logical[row] = -1;
+        freed_phys[row] = -1;
+      }
+      continue;
+    }
+    int32_t* bt = block_table + row * max_blocks;
+    float* out = scores_out != nullptr ? scores_out + row * max_blocks : nullptr;
+    uint4 kb[2][NL], vb[2][NL];
+    float best = 0.f;
+    int jstar = 0;
+    PS::issue(kb[0], vb[0], k_pool, v_pool, bt[0], lane);
+    for (int j = 0; j < n; j += 2) {
+      // unconditional issues (the last ones re-read the row's last page) keep the load order known
+      PS::issue(kb[1], vb[1], k_pool, v_pool, bt[j + 1 < n ? j + 1 : n - 1], lane);
+      const float s0 = PS::finish(kb[0], vb[0], lane);
+      if (j == 0 || s0 < best) {
+        best = s0;
+        jstar = j;
+      }
+      if (out != nullptr && lane == 0) out[j] = s0;
+      PS::issue(kb[0], vb[0], k_pool, v_pool, bt[j + 2 < n ? j + 2 : n - 1], lane);
+      if (j + 1 < n) {
+        const float s1 = PS::finish(kb[1], vb[1], lane);
+        if (s1 < best) {
+          best = s1;
+          jstar = j + 1;
+        }
+        if (out != nullptr && lane == 0) out[j + 1] = s1;
+      }
+    }
+    if (out != nullptr)
+      for (int j = n + lane; j < max_blocks; j += kWave) out[j] = __builtin_inff();
+    __builtin_amdgcn_s_waitcnt(0);  // the trailing re-read of the last page has landed before the row moves
+    const int freed = compact_row(bt, nullptr, jstar, n, lane);
+    if (lane == 0) {
+      evicted_logical[row] = jstar;
+      freed_phys[row] = freed;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0 && trigger) seq_lens[s] = len - B;
 }
 
 template <typename T, int D, int B>
@@ -107,7 +189,33 @@ hipError_t launch(const ScoreArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+template <typename T, int D, int B>
+hipError_t launch_fused(const ScoreEvictArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL((score_evict_kernel<T, D, B>), dim3((unsigned)a.num_seqs), dim3(kThreads), 0, stream,
+                     (const T*)a.k_pool, (const T*)a.v_pool, a.block_table, a.seq_lens, a.scores_out,
+                     a.evicted_logical, a.freed_phys, a.num_kv_heads, a.max_blocks, a.budget);
+  return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_score_evict(const ScoreEvictArgs& a, hipStream_t stream) {
+#define PE_CASE(TT, DD, BB) \
+  if (a.head_dim == DD && a.block_size == BB) return launch_fused<TT, DD, BB>(a, stream)
+  if (a.is_bf16) {
+    PE_CASE(bf16_t, 64, 16);
+    PE_CASE(bf16_t, 64, 32);
+    PE_CASE(bf16_t, 128, 16);
+    PE_CASE(bf16_t, 128, 32);
+  } else {
+    PE_CASE(float, 64, 16);
+    PE_CASE(float, 64, 32);
+    PE_CASE(float, 128, 16);
+    PE_CASE(float, 128, 32);
+  }
+#undef PE_CASE
+  return hipErrorInvalidValue;
+}
 
 hipError_t launch_score_blocks(const ScoreArgs& a, hipStream_t stream) {
 #define PE_CASE(TT, DD, BB) \

@@ -98,7 +98,7 @@ class GraphedStepper:
                 recent = -1
             else:
                 recent = max(n // e.B - sc for n, sc in zip(e.host_lens * e.layers, f.host_scored))
-        return (f.seq_lens.data_ptr(), trig, e.fused, f.cached_scores, recent)
+        return (f.seq_lens.data_ptr(), trig, e.fused, f.cached_scores, f.fused_evict, recent)
 
     def step(self) -> bool:
         key = self._key()

@@ -60,8 +60,11 @@ def test_null_pointers_and_bad_budget():
     assert L.pe_score_blocks(ctypes.byref(d), None, FAKE, FAKE, FAKE, FAKE, None, 0, None) == pe.PE_ERR_INVALID_ARG
     assert L.pe_score_blocks(None, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None) == pe.PE_ERR_INVALID_ARG
     assert L.pe_evict_blocks(ctypes.byref(d), FAKE, FAKE, None, 256, FAKE, FAKE, None) == pe.PE_ERR_INVALID_ARG
+    assert L.pe_score_evict(ctypes.byref(d), FAKE, FAKE, FAKE, None, 256, None, FAKE, FAKE, None) == pe.PE_ERR_INVALID_ARG
+    assert L.pe_score_evict(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, 256, None, None, FAKE, None) == pe.PE_ERR_INVALID_ARG
     for bad in (0, -16, 250):
         assert L.pe_evict_blocks(ctypes.byref(d), FAKE, FAKE, FAKE, bad, FAKE, FAKE, None) == pe.PE_ERR_INVALID_ARG
+        assert L.pe_score_evict(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, bad, None, FAKE, FAKE, None) == pe.PE_ERR_INVALID_ARG
         assert L.pe_prefill_prune(ctypes.byref(d), FAKE, FAKE, FAKE, 1000, 1000, bad, FAKE, FAKE, FAKE, FAKE, None,
                                   FAKE, 1 << 30, None) == pe.PE_ERR_INVALID_ARG
     assert L.pe_paged_decode(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, ctypes.c_float(float("nan")), FAKE, FAKE,

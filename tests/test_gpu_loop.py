@@ -30,7 +30,8 @@ def _compare_state(cache_gpu, cache_cpu, where):
     assert np.array_equal(cache_gpu.spare_used.cpu().numpy(), cache_cpu.spare_used), where
 
 
-def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=False, evict_opts=None):
+def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=False, evict_opts=None,
+             fused_evict=False):
     """One layer of workload `wl`: prune, then `steps` decode steps on both sides, compared every step."""
     lens = synth.context_lengths(wl, SEED)
     k_in, v_in, cu = synth.prompt_kv(wl, layer, lens, SEED)
@@ -43,6 +44,7 @@ def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=Fals
     gcache.prefill_prune(k_in.to(DEV), v_in.to(DEV), cu.to(DEV), max(lens), kept)
     gcache.set_host_lens(lens)
     gcache.cached_scores = cached_scores
+    gcache.fused_evict = fused_evict  # decisions only: the one-launch form is not asked for the scores here
     if evict_opts is not None:
         gcache.evict_opts = pe.pe_evict_opts(evict_opts.get("policy", 0), evict_opts.get("protect_first", 0),
                                              evict_opts.get("protect_last", 0), int(evict_opts.get("share_heads", False)), 0)
@@ -68,7 +70,7 @@ def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=Fals
         assert (oev >= 0).any() == triggered, where
         if triggered:
             n_evictions += 1
-        if triggered and oscores is not None:
+        if triggered and oscores is not None and not fused_evict:
             gs = gcache.scores.cpu().numpy()
             if cached_scores:   # the kept array has already lost the evicted entry of every row that evicted
                 want_sc = oscores.copy()
@@ -118,6 +120,16 @@ def test_cached_scores_give_the_same_decisions(wl, steps, n_want):
     equal the oracle's full re-scoring at every trigger, and so must every decision."""
     print("case loop cached scores", wl.name, flush=True)
     n_ev, _ = run_loop(wl, steps, cached_scores=True)
+    assert n_ev == n_want
+
+
+@pytest.mark.parametrize("wl,steps,n_want", [(synth.TINY, 70, 5), (synth.LLAMA32_1B.with_(budget=512), 36, 3),
+                                             (synth.LLAMA31_8B.with_(num_seqs=6, budget=1024), 20, 2)])
+def test_score_and_evict_in_one_launch(wl, steps, n_want):
+    """pe_score_evict in place of pe_score_blocks + pe_evict_blocks: same tables, lengths, evicted pages and
+    attention outputs as the oracle at every step."""
+    print("case loop fused score+evict", wl.name, flush=True)
+    n_ev, _ = run_loop(wl, steps, fused_evict=True, check_pool=wl.num_seqs <= 8)
     assert n_ev == n_want
 
 

@@ -102,6 +102,81 @@ def test_score_blocks_closed_forms():
     assert got[0, 0, 1] == np.float32(exact) and np.isinf(got[0, 1, 2])
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("B", [16, 32])
+@pytest.mark.parametrize("want_scores", [True, False])
+def test_score_evict_one_launch(dt, D, B, want_scores):
+    """pe_score_evict against oracle score_blocks + evict_blocks: odd and even page counts, one page, a partial
+    tail (no trigger), under budget (no trigger), an empty row, more rows than waves (Hk = 5)."""
+    print("case score_evict", dt, D, B, want_scores, flush=True)
+    Hk, C = 5, 2 * B
+    lens = [37 * B, 20 * B + 5, 0, B, 16 * B, 2 * B, 3 * B, 65 * B]
+    k_pool, v_pool, table, sl = make_paged(900 + D + B, lens, Hk, D, B, DTYPES[dt], extra=2)
+    S, _, mb = table.shape
+    P = k_pool.shape[0]
+    desc = pe.make_desc(k_pool.dtype, S, Hk, Hk, D, B, mb, P)
+    t_gpu, l_gpu = table.to(DEV), sl.to(DEV)
+    sc_gpu = torch.full((S, Hk, mb), -123.0, dtype=torch.float32, device=DEV)
+    ev_gpu = torch.full((S, Hk), -7, dtype=torch.int32, device=DEV)
+    fr_gpu = torch.full((S, Hk), -7, dtype=torch.int32, device=DEV)
+    kd, vd = k_pool.to(DEV), v_pool.to(DEV)
+    o_table, o_lens = i32(table).copy(), i32(sl).copy()
+    for call in range(2):   # the second call sees the shrunken rows: only rows still at budget go again
+        trig = [(L > 0 and L % B == 0 and L >= C) for L in o_lens]
+        want_sc = oracle.score_blocks(f32(k_pool), f32(v_pool), o_table, o_lens)
+        pe.pe_score_evict(desc, kd, vd, t_gpu, l_gpu, C, sc_gpu if want_scores else None, ev_gpu, fr_gpu)
+        torch.cuda.synchronize()
+        if want_scores:
+            got_sc = sc_gpu.cpu().numpy()
+            for s in range(S):
+                if not trig[s]:
+                    assert np.all(got_sc[s] == np.float32(-123.0)), "rows of idle sequences stay untouched"
+                    continue
+                assert np.array_equal(np.isinf(got_sc[s]), np.isinf(want_sc[s]))
+                fin = np.isfinite(want_sc[s])
+                assert _ulp_diff(got_sc[s][fin], want_sc[s][fin]).max() <= 1
+            # the decision, taken on the scores the kernel itself reports
+            dec_sc = np.where(np.array(trig)[:, None, None], got_sc, want_sc).astype(np.float32)
+            t2, l2 = o_table.copy(), o_lens.copy()
+            ev2, fr2 = oracle.evict_blocks(dec_sc, t2, l2, B, C)
+            assert np.array_equal(ev_gpu.cpu().numpy(), ev2) and np.array_equal(fr_gpu.cpu().numpy(), fr2)
+        ev, fr = oracle.evict_blocks(want_sc, o_table, o_lens, B, C)
+        assert np.array_equal(ev_gpu.cpu().numpy(), ev), call
+        assert np.array_equal(fr_gpu.cpu().numpy(), fr), call
+        assert np.array_equal(t_gpu.cpu().numpy(), o_table), call
+        assert np.array_equal(l_gpu.cpu().numpy(), o_lens), call
+        assert sum(trig) == (5 if call == 0 else 4)
+        sc_gpu.fill_(-123.0)
+
+
+def test_score_evict_ties_and_planted_minimum():
+    """All pages equal (V = K, score exactly 1) -> page 0 goes; a planted low page at the end of an odd row, at
+    the end of an even row and in the middle -> exactly that page goes."""
+    print("case score_evict ties", flush=True)
+    B, D, Hk = 16, 128, 2
+    lens = [9 * B, 10 * B, 33 * B]
+    k_pool, _, table, sl = make_paged(77, lens, Hk, D, B, torch.bfloat16)
+    v_pool = k_pool.clone()
+    plant = {(0, 0): 8, (1, 1): 9, (2, 0): 17}   # (sequence, head) -> logical page with V halved
+    for (s, h), j in plant.items():
+        v_pool[int(table[s, h, j])] *= 0.5
+    S, _, mb = table.shape
+    desc = pe.make_desc(k_pool.dtype, S, Hk, Hk, D, B, mb, k_pool.shape[0])
+    t_gpu, l_gpu = table.to(DEV), sl.to(DEV)
+    ev_gpu = torch.full((S, Hk), -7, dtype=torch.int32, device=DEV)
+    fr_gpu = torch.full((S, Hk), -7, dtype=torch.int32, device=DEV)
+    pe.pe_score_evict(desc, k_pool.to(DEV), v_pool.to(DEV), t_gpu, l_gpu, 2 * B, None, ev_gpu, fr_gpu)
+    torch.cuda.synchronize()
+    ev = ev_gpu.cpu().numpy()
+    for s in range(S):
+        for h in range(Hk):
+            j = plant.get((s, h), 0)
+            assert ev[s, h] == j
+            assert fr_gpu[s, h].item() == int(table[s, h, j])
+    assert l_gpu.cpu().tolist() == [L - B for L in lens]
+
+
 def test_evict_blocks_bit_exact():
     print("case evict_blocks_bit_exact", flush=True)
     rng = np.random.default_rng(300)
