@@ -46,6 +46,7 @@ def parse_args():
                     help="score + evict of a trigger step in one launch (pe_score_evict)")
     ap.add_argument("--graph", action="store_true", help="replay each step from captured HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-breakdown", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=16)
     ap.add_argument("--cpu-layers", type=int, default=2)
     ap.add_argument("--cpu-steps", type=int, default=33)
@@ -135,6 +136,60 @@ def cpu_baseline(wl, seed, n_seqs, n_layers, steps):
                       "(an eviction every %d steps, the first at step 1), %.1f s wall; scaled to all layers"
                       % (S, wl.num_seqs, n_layers, wl.layers, steps, wl.block_size, dt),
             "ms_per_layer_step": per_layer_step * 1e3}
+
+
+def kernel_breakdown(eng, wl, new_k, new_v, q, out):
+    """Every kernel of the path on its own, after the timed region (not part of `value`): the loop is advanced to
+    the next trigger step, which is then issued call by call (score, evict, then per layer append and attention
+    as separate launches) with an event after each call."""
+    import torch
+
+    L, S, Hk, D, B = wl.layers, wl.num_seqs, wl.num_kv_heads, wl.head_dim, wl.block_size
+    elem = 2 if wl.dtype == "bf16" else 4
+    guard = 0
+    while not any(eng._triggers()):
+        eng.decode_step(new_k, new_v, q, out)
+        guard += 1
+        if guard > 4 * B + wl.budget:
+            return None
+    trig = eng._triggers()
+    f = eng.folded
+
+    def ev():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record()
+        return e
+
+    full_pages = sum(n // B for n in eng.host_lens)
+    torch.cuda.synchronize()
+    e0 = ev()
+    f.score_blocks()
+    e1 = ev()
+    f.evict_blocks()
+    e2 = ev()
+    eng.host_lens = [n - B if t else n for n, t in zip(eng.host_lens, trig)]
+    marks = []
+    for l, c in enumerate(eng.per_layer):
+        a = ev()
+        c.append_kv(new_k[l], new_v[l])
+        b = ev()
+        c.paged_decode(q[l], out[l])
+        marks.append((a, b, ev()))
+    eng.host_lens = [n + 1 for n in eng.host_lens]
+    torch.cuda.synchronize()
+    score_us = e0.elapsed_time(e1) * 1e3
+    score_bytes = L * Hk * full_pages * B * D * 2 * elem
+    app = sorted(a.elapsed_time(b) * 1e3 for a, b, _ in marks)
+    att = sorted(b.elapsed_time(c_) * 1e3 for _, b, c_ in marks)
+    att_bytes = sum(eng.host_lens) * Hk * D * 2 * elem
+    med = lambda v: v[len(v) // 2]
+    return {"note": "one trigger step issued call by call after the timed region; event-to-event times, each "
+                    "includes its launch gap",
+            "score_blocks": {"us": score_us, "bytes": score_bytes, "GBps": score_bytes / score_us / 1e3},
+            "evict_blocks": {"us": e1.elapsed_time(e2) * 1e3, "rows": L * S * Hk},
+            "append_kv": {"us_median_per_layer": med(app)},
+            "paged_decode": {"us_median_per_layer": med(att), "bytes": att_bytes,
+                             "GBps": att_bytes / med(att) / 1e3}}
 
 
 def main():
@@ -276,6 +331,9 @@ def main():
         total_bytes = mean_cached * L * args.steps + score_bytes * n_trigger
         result["path_GBps"] = total_bytes / elapsed / 1e9
         result["path_frac_of_hbm_peak"] = result["path_GBps"] / HBM_PEAK_GBS
+
+    result["kernels"] = None if (args.graph or args.no_kernel_breakdown) else kernel_breakdown(
+        eng, wl, new_k[0], new_v[0], q[0], out)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
