@@ -30,6 +30,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="llama31_8b")
     ap.add_argument("--budget", type=int, default=None)
+    ap.add_argument("--block-size", type=int, default=None, help="override the page size (16, 32, 64, 128)")
     ap.add_argument("--q-heads", type=int, default=None, help="override the number of query heads (group size probe)")
     ap.add_argument("--seed", type=int, default=2509)
     ap.add_argument("--splits", type=int, default=None, help="override the split count of pe_paged_decode")
@@ -205,6 +206,8 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     if args.budget is not None:
         wl = wl.with_(budget=args.budget)
+    if args.block_size is not None:
+        wl = wl.with_(block_size=args.block_size)
     if args.q_heads is not None:
         wl = wl.with_(num_q_heads=args.q_heads)
     dev = "cuda:0"

@@ -65,7 +65,7 @@ typedef struct pe_cache_desc {
   int32_t num_kv_heads;    /* Hk >= 1 */
   int32_t num_q_heads;     /* Hq, a multiple of Hk with Hq/Hk <= 8; q head h reads KV head h/(Hq/Hk) */
   int32_t head_dim;        /* D: 64 or 128 */
-  int32_t block_size;      /* B: 16 or 32 tokens per page */
+  int32_t block_size;      /* B: 16, 32, 64 or 128 tokens per page */
   int32_t max_blocks;      /* row stride of block_table and of the score array */
   int64_t num_phys_blocks; /* P: pages in each pool */
 } pe_cache_desc;

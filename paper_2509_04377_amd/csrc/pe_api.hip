@@ -20,7 +20,8 @@ int check_desc(const pe_cache_desc* d) {
   if (d->num_q_heads % d->num_kv_heads != 0) return PE_ERR_INVALID_ARG;
   if (d->num_q_heads / d->num_kv_heads > 8) return PE_ERR_UNSUPPORTED;
   if (d->head_dim != 64 && d->head_dim != 128) return PE_ERR_UNSUPPORTED;
-  if (d->block_size != 16 && d->block_size != 32) return PE_ERR_UNSUPPORTED;
+  if (d->block_size != 16 && d->block_size != 32 && d->block_size != 64 && d->block_size != 128)
+    return PE_ERR_UNSUPPORTED;
   if (d->num_phys_blocks > 0x7fffffffLL) return PE_ERR_UNSUPPORTED;
   if ((int64_t)d->num_seqs * d->num_kv_heads > 0x7fffffffLL / 64) return PE_ERR_UNSUPPORTED;
   return PE_OK;

@@ -20,20 +20,21 @@ constexpr int kWaves = kThreads / kWave;
 constexpr int kPagesPerWave = 4;
 constexpr int kPagesPerGroup = kWaves * kPagesPerWave;
 
-// One page scored by one wave.
-template <typename T, int D, int B>
-struct PageScore {
+// A chunk of CH token rows (a whole page, or 32 tokens of a larger one) scored by one wave.
+template <typename T, int D, int CH>
+struct ChunkScore {
   using G = RowGeom<T, D>;
   static constexpr int LPR = G::kLanesPerRow;
   static constexpr int TPL = G::kTokensPerLoad;
-  static constexpr int NL = B / TPL;  // wave-loads per page
-  static constexpr int NV = 2 * NL;   // per-lane partial sums: (K, V) x NL token rows
+  static constexpr int NL = CH / TPL;  // wave-loads per chunk
+  static constexpr int NV = 2 * NL;    // per-lane partial sums: (K, V) x NL token rows
   static_assert(NV <= LPR, "reduce-scatter needs at least as many lanes per row as values");
-  static constexpr int kVecPerPage = B * D / G::kPerVec;
+  static constexpr int kVecPerChunk = CH * D / G::kPerVec;
 
+  // vec_base: index (in 16-byte units) of the chunk's first element
   static __device__ __forceinline__ void issue(uint4 (&kb)[NL], uint4 (&vb)[NL], const T* k_pool, const T* v_pool,
-                                               int phys, int lane) {
-    const int64_t base = (int64_t)phys * kVecPerPage + lane;
+                                               int64_t vec_base, int lane) {
+    const int64_t base = vec_base + lane;
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
       kb[i] = load_vec_stream(k_pool, base + i * kWave);
@@ -41,8 +42,9 @@ struct PageScore {
     }
   }
 
-  // The page's score (the same value in every lane): fp64 throughout, one rounding to fp32.
-  static __device__ __forceinline__ float finish(const uint4 (&kb)[NL], const uint4 (&vb)[NL], int lane) {
+  // sum + the chunk's token ratios, added in slot order (the same value in every lane); fp64 throughout.
+  static __device__ __forceinline__ double add_ratios(const uint4 (&kb)[NL], const uint4 (&vb)[NL], int lane,
+                                                      double sum) {
     // value index = kv * NL + i  (kv: 0 = K, 1 = V; i = wave-load = token row i*TPL + lane/LPR)
     double part[NV];
 #pragma unroll
@@ -51,10 +53,9 @@ struct PageScore {
       part[NL + i] = sumsq_vec<T>(vb[i], 0.0);
     }
     const double ratio = token_ratio_from_partials<NL, LPR>(part, lane);
-    // page mean, summed in slot order t = 0 .. B-1; token t = i*TPL + g sits on lane g*LPR + 2*bitrev(i)
-    double sum = 0.0;
+    // token t = i*TPL + g sits on lane g*LPR + 2*bitrev(i)
 #pragma unroll
-    for (int t = 0; t < B; ++t) {
+    for (int t = 0; t < CH; ++t) {
       constexpr int kBits = ilog2(NL);
       const int i = t / TPL, g = t % TPL;
       const int src = g * LPR + 2 * bit_reverse<kBits>(i);
@@ -62,7 +63,19 @@ struct PageScore {
       const int hi = __builtin_amdgcn_readlane(__double2hiint(ratio), src);
       sum += __hiloint2double(hi, lo);
     }
-    return (float)(sum / (double)B);
+    return sum;
+  }
+};
+
+// Pages of more than 32 tokens are swept as chunks of 32; the page mean is still one sum in slot order.
+template <typename T, int D, int B>
+struct PageGeom {
+  static constexpr int CH = B < 32 ? B : 32;
+  static constexpr int NCH = B / CH;
+  using CS = ChunkScore<T, D, CH>;
+  static constexpr int64_t kVecPerPage = (int64_t)NCH * CS::kVecPerChunk;
+  static __device__ __forceinline__ int64_t chunk_base(int phys, int c) {
+    return (int64_t)phys * kVecPerPage + (int64_t)c * CS::kVecPerChunk;
   }
 };
 
@@ -73,8 +86,11 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
                                                                 const int32_t* __restrict__ seq_lens,
                                                                 float* __restrict__ scores, int num_kv_heads,
                                                                 int max_blocks, int groups_per_row, int recent) {
-  using PS = PageScore<T, D, B>;
-  constexpr int NL = PS::NL;
+  using PG = PageGeom<T, D, B>;
+  using CS = typename PG::CS;
+  constexpr int NL = CS::NL;
+  constexpr int NCH = PG::NCH;
+  constexpr int kUnits = kPagesPerWave * NCH;  // (page, chunk) units of one wave, in order
 
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
@@ -91,19 +107,25 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
   const int j0 = j_first + grp * kPagesPerGroup + wave;
 
   uint4 kb[2][NL], vb[2][NL];
-  if (j0 < nfull) PS::issue(kb[0], vb[0], k_pool, v_pool, bt[j0], lane);
+  if (j0 < nfull) CS::issue(kb[0], vb[0], k_pool, v_pool, PG::chunk_base(bt[j0], 0), lane);
+  double sum = 0.0;
 #pragma unroll
-  for (int it = 0; it < kPagesPerWave; ++it) {
-    const int j = j0 + it * kWaves;
-    if (it + 1 < kPagesPerWave && j + kWaves < nfull)
-      PS::issue(kb[(it + 1) & 1], vb[(it + 1) & 1], k_pool, v_pool, bt[j + kWaves], lane);
+  for (int u = 0; u < kUnits; ++u) {
+    const int j = j0 + (u / NCH) * kWaves;
+    if (u + 1 < kUnits) {
+      const int jn = j0 + ((u + 1) / NCH) * kWaves;
+      if (jn < nfull) CS::issue(kb[(u + 1) & 1], vb[(u + 1) & 1], k_pool, v_pool, PG::chunk_base(bt[jn], (u + 1) % NCH), lane);
+    }
     if (j >= j_end) break;
     if (j >= nfull) {
-      if (lane == 0) out[j] = __builtin_inff();
+      if (lane == 0 && u % NCH == 0) out[j] = __builtin_inff();
       continue;
     }
-    const float sc = PS::finish(kb[it & 1], vb[it & 1], lane);
-    if (lane == 0) out[j] = sc;
+    sum = CS::add_ratios(kb[u & 1], vb[u & 1], lane, sum);
+    if (u % NCH == NCH - 1) {
+      if (lane == 0) out[j] = (float)(sum / (double)B);  // one rounding to fp32
+      sum = 0.0;
+    }
   }
 }
 
@@ -120,8 +142,10 @@ __global__ __launch_bounds__(kThreads) void score_evict_kernel(const T* __restri
                                                                int32_t* __restrict__ evicted_logical,
                                                                int32_t* __restrict__ freed_phys, int num_kv_heads,
                                                                int max_blocks, int budget) {
-  using PS = PageScore<T, D, B>;
-  constexpr int NL = PS::NL;
+  using PG = PageGeom<T, D, B>;
+  using CS = typename PG::CS;
+  constexpr int NL = CS::NL;
+  constexpr int NCH = PG::NCH;
   const int s = (int)blockIdx.x;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
@@ -143,29 +167,42 @@ __global__ __launch_bounds__(kThreads) void score_evict_kernel(const T* __restri
     uint4 kb[2][NL], vb[2][NL];
     float best = 0.f;
     int jstar = 0;
-    PS::issue(kb[0], vb[0], k_pool, v_pool, bt[0], lane);
-    for (int j = 0; j < n; j += 2) {
-      // unconditional issues (the last ones re-read the row's last page) keep the load order known
-      PS::issue(kb[1], vb[1], k_pool, v_pool, bt[j + 1 < n ? j + 1 : n - 1], lane);
-      const float s0 = PS::finish(kb[0], vb[0], lane);
-      if (j == 0 || s0 < best) {
-        best = s0;
+    double sum = 0.0;
+    const int units = n * NCH;  // (page, chunk) units in logical order; unit u = page u / NCH, chunk u % NCH
+    // a page is complete after its last chunk: round once, compare, report
+    auto page_done = [&](int u) {
+      if (u % NCH != NCH - 1) return;
+      const int j = u / NCH;
+      const float sc = (float)(sum / (double)B);
+      sum = 0.0;
+      if (j == 0 || sc < best) {
+        best = sc;
         jstar = j;
       }
-      if (out != nullptr && lane == 0) out[j] = s0;
-      PS::issue(kb[0], vb[0], k_pool, v_pool, bt[j + 2 < n ? j + 2 : n - 1], lane);
-      if (j + 1 < n) {
-        const float s1 = PS::finish(kb[1], vb[1], lane);
-        if (s1 < best) {
-          best = s1;
-          jstar = j + 1;
-        }
-        if (out != nullptr && lane == 0) out[j + 1] = s1;
+      if (out != nullptr && lane == 0) out[j] = sc;
+    };
+    // unconditional issues (those past the end re-read the row's last unit) keep the load order known
+    auto issue_unit = [&](int buf, int u) {
+      const int uc = u < units ? u : units - 1;
+      if (buf == 0)
+        CS::issue(kb[0], vb[0], k_pool, v_pool, PG::chunk_base(bt[uc / NCH], uc % NCH), lane);
+      else
+        CS::issue(kb[1], vb[1], k_pool, v_pool, PG::chunk_base(bt[uc / NCH], uc % NCH), lane);
+    };
+    issue_unit(0, 0);
+    for (int u = 0; u < units; u += 2) {
+      issue_unit(1, u + 1);
+      sum = CS::add_ratios(kb[0], vb[0], lane, sum);
+      page_done(u);
+      issue_unit(0, u + 2);
+      if (u + 1 < units) {
+        sum = CS::add_ratios(kb[1], vb[1], lane, sum);
+        page_done(u + 1);
       }
     }
     if (out != nullptr)
       for (int j = n + lane; j < max_blocks; j += kWave) out[j] = __builtin_inff();
-    __builtin_amdgcn_s_waitcnt(0);  // the trailing re-read of the last page has landed before the row moves
+    __builtin_amdgcn_s_waitcnt(0);  // the trailing re-reads have landed before the row moves
     const int freed = compact_row(bt, nullptr, jstar, n, lane);
     if (lane == 0) {
       evicted_logical[row] = jstar;
@@ -202,17 +239,19 @@ hipError_t launch_fused(const ScoreEvictArgs& a, hipStream_t stream) {
 hipError_t launch_score_evict(const ScoreEvictArgs& a, hipStream_t stream) {
 #define PE_CASE(TT, DD, BB) \
   if (a.head_dim == DD && a.block_size == BB) return launch_fused<TT, DD, BB>(a, stream)
+#define PE_CASES(TT, DD) \
+  PE_CASE(TT, DD, 16);   \
+  PE_CASE(TT, DD, 32);   \
+  PE_CASE(TT, DD, 64);   \
+  PE_CASE(TT, DD, 128)
   if (a.is_bf16) {
-    PE_CASE(bf16_t, 64, 16);
-    PE_CASE(bf16_t, 64, 32);
-    PE_CASE(bf16_t, 128, 16);
-    PE_CASE(bf16_t, 128, 32);
+    PE_CASES(bf16_t, 64);
+    PE_CASES(bf16_t, 128);
   } else {
-    PE_CASE(float, 64, 16);
-    PE_CASE(float, 64, 32);
-    PE_CASE(float, 128, 16);
-    PE_CASE(float, 128, 32);
+    PE_CASES(float, 64);
+    PE_CASES(float, 128);
   }
+#undef PE_CASES
 #undef PE_CASE
   return hipErrorInvalidValue;
 }
@@ -220,17 +259,19 @@ hipError_t launch_score_evict(const ScoreEvictArgs& a, hipStream_t stream) {
 hipError_t launch_score_blocks(const ScoreArgs& a, hipStream_t stream) {
 #define PE_CASE(TT, DD, BB) \
   if (a.head_dim == DD && a.block_size == BB) return launch<TT, DD, BB>(a, stream)
+#define PE_CASES(TT, DD) \
+  PE_CASE(TT, DD, 16);   \
+  PE_CASE(TT, DD, 32);   \
+  PE_CASE(TT, DD, 64);   \
+  PE_CASE(TT, DD, 128)
   if (a.is_bf16) {
-    PE_CASE(bf16_t, 64, 16);
-    PE_CASE(bf16_t, 64, 32);
-    PE_CASE(bf16_t, 128, 16);
-    PE_CASE(bf16_t, 128, 32);
+    PE_CASES(bf16_t, 64);
+    PE_CASES(bf16_t, 128);
   } else {
-    PE_CASE(float, 64, 16);
-    PE_CASE(float, 64, 32);
-    PE_CASE(float, 128, 16);
-    PE_CASE(float, 128, 32);
+    PE_CASES(float, 64);
+    PE_CASES(float, 128);
   }
+#undef PE_CASES
 #undef PE_CASE
   return hipErrorInvalidValue;
 }

@@ -123,6 +123,15 @@ def test_cached_scores_give_the_same_decisions(wl, steps, n_want):
     assert n_ev == n_want
 
 
+@pytest.mark.parametrize("B,fused_evict", [(64, False), (128, False), (64, True)])
+def test_larger_pages(B, fused_evict):
+    """Pages of 64 and 128 tokens (the method is stated for any page size): the whole loop against the oracle."""
+    print("case loop larger pages", B, fused_evict, flush=True)
+    wl = synth.LLAMA32_1B.with_(block_size=B, budget=1024, num_seqs=4)
+    n_ev, _ = run_loop(wl, 2 * B + 3, fused_evict=fused_evict)
+    assert n_ev == 3
+
+
 @pytest.mark.parametrize("wl,steps,n_want", [(synth.TINY, 70, 5), (synth.LLAMA32_1B.with_(budget=512), 36, 3),
                                              (synth.LLAMA31_8B.with_(num_seqs=6, budget=1024), 20, 2)])
 def test_score_and_evict_in_one_launch(wl, steps, n_want):

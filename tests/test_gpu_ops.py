@@ -58,7 +58,7 @@ def gpu_scores(k_pool, v_pool, table, lens, Hq=None):
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("D", [64, 128])
-@pytest.mark.parametrize("B", [16, 32])
+@pytest.mark.parametrize("B", [16, 32, 64, 128])
 def test_score_blocks_random(dt, D, B):
     print("case score_blocks_random", dt, D, B, flush=True)
     # 37 pages per row at most: three 16-page groups with a ragged tail; a partial tail page; an empty row
@@ -104,7 +104,7 @@ def test_score_blocks_closed_forms():
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("D", [64, 128])
-@pytest.mark.parametrize("B", [16, 32])
+@pytest.mark.parametrize("B", [16, 32, 64, 128])
 @pytest.mark.parametrize("want_scores", [True, False])
 def test_score_evict_one_launch(dt, D, B, want_scores):
     """pe_score_evict against oracle score_blocks + evict_blocks: odd and even page counts, one page, a partial
@@ -216,7 +216,7 @@ def test_evict_blocks_bit_exact():
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
-@pytest.mark.parametrize("D,B", [(64, 16), (128, 16), (64, 32), (128, 32)])
+@pytest.mark.parametrize("D,B", [(64, 16), (128, 16), (64, 32), (128, 32), (128, 64), (64, 128)])
 @pytest.mark.parametrize("G", [1, 2, 3, 4, 6, 8])
 def test_paged_decode_shapes(dt, D, B, G):
     print("case paged_decode_shapes", dt, D, B, G, flush=True)
@@ -317,7 +317,7 @@ def _prune_both(k, v, cu, lens, Hk, D, B, C, dtype, seed):
 def test_prefill_prune_ragged(dt, D):
     print("case prefill_prune_ragged", dt, D, flush=True)
     lens = [1, 100, 1023, 1024, 1025, 3000, 5000, 256]
-    for C, B in ((256, 16), (1024, 32)):
+    for C, B in ((256, 16), (1024, 32), (512, 64), (1024, 128)):
         k, v, cu = _prompt(600 + D + C, lens, 2, D, DTYPES[dt])
         _prune_both(k, v, cu, lens, 2, D, B, C, DTYPES[dt], 601)
 
@@ -364,7 +364,8 @@ def test_append_kv_matches_oracle():
 
 
 @pytest.mark.parametrize("dt,D,B,G", [("bf16", 128, 16, 4), ("bf16", 64, 16, 4), ("f32", 64, 16, 2), ("bf16", 128, 32, 3),
-                                      ("f32", 128, 32, 1), ("bf16", 64, 32, 8)])
+                                      ("f32", 128, 32, 1), ("bf16", 64, 32, 8), ("bf16", 128, 64, 4),
+                                      ("f32", 64, 128, 2)])
 def test_append_paged_decode_fused(dt, D, B, G):
     """The one-launch append + attention against the oracle's append followed by its attention, three
     steps in a row: tables, lengths, spare/freed bookkeeping and pool contents bit-exact, output in
