@@ -59,6 +59,17 @@ typedef enum {
   PE_OP_APPEND_PAGED_DECODE = 4
 } pe_op;
 
+/* Cache layout (Sec. 2.4 leaves the granularity open).
+ * PE_LAYOUT_PER_HEAD (default): a row is one (sequence, KV head); every row owns a block-table row and its
+ *   pages; a page holds [B][D] elements of one head; decisions are per row.
+ * PE_LAYOUT_SHARED: the layout of a stock paged cache.  ONE table row per sequence, a page holds
+ *   [B][Hk][D] (token slot, head, element), ONE decision per sequence: a token's / page's score is the mean
+ *   over the KV heads of the per-head fp32 scores (summed in head order in fp64, rounded once), and the token
+ *   / page is dropped for all heads.  Array shapes then lose their Hk dimension where the documentation
+ *   below says so ("shared: ...").  pe_append_paged_decode and pe_score_evict are per-head only
+ *   (PE_ERR_UNSUPPORTED otherwise). */
+typedef enum { PE_LAYOUT_PER_HEAD = 0, PE_LAYOUT_SHARED = 1 } pe_layout;
+
 typedef struct pe_cache_desc {
   int32_t dtype;           /* pe_dtype of q, pools, k_in/v_in, out */
   int32_t num_seqs;        /* S >= 1 */
@@ -68,6 +79,7 @@ typedef struct pe_cache_desc {
   int32_t block_size;      /* B: 16, 32, 64 or 128 tokens per page */
   int32_t max_blocks;      /* row stride of block_table and of the score array */
   int64_t num_phys_blocks; /* P: pages in each pool */
+  int32_t layout;          /* pe_layout; 0 when the struct is zero- or positionally initialised up to P */
 } pe_cache_desc;
 
 /* Bytes of device workspace `op` needs for `desc`.  `total_tokens` is the packed prompt length
@@ -101,6 +113,8 @@ int pe_get_option(int key);
  *     is +INF.  A token with ||V|| = 0 contributes 0; otherwise ||K|| = 0 contributes +INF.
  *     scores_out: [S][Hk][max_blocks] fp32, fully overwritten.  Reads pools/table/lens only.
  *     workspace: none needed (may be NULL / 0).
+ *     shared: block_table is [S][max_blocks]; scores_out keeps its shape and holds the per-head page scores
+ *     (the head mean is taken where the decision is, in (3)).
  */
 int pe_score_blocks(const pe_cache_desc* desc, const void* k_pool, const void* v_pool,
                     const int32_t* block_table, const int32_t* seq_lens, float* scores_out, void* workspace,
@@ -121,6 +135,9 @@ int pe_score_blocks(const pe_cache_desc* desc, const void* k_pool, const void* v
  *     kept_idx_out: NULL, or [S][Hk][budget_tokens] int32 that receives the in-sequence indices of the
  *     kept tokens in ascending order, -1 padded.
  *     workspace: pe_workspace_bytes(PE_OP_PREFILL_PRUNE, desc, total_tokens).
+ *     shared: a token's score is the head mean of its per-head fp32 scores, one selection per sequence, the
+ *     survivors' rows of all heads go to page block_table[s][i / B], slot i % B; block_table [S][max_blocks],
+ *     kept_idx_out [S][budget_tokens].
  */
 int pe_prefill_prune(const pe_cache_desc* desc, const void* k_in, const void* v_in, const int32_t* cu_seqlens,
                      int64_t total_tokens, int32_t max_seqlen, int32_t budget_tokens, void* k_pool,
@@ -137,6 +154,9 @@ int pe_prefill_prune(const pe_cache_desc* desc, const void* k_in, const void* v_
  *     removed, or -1 for rows that did not evict.  seq_lens[s] -= B, once per triggering sequence.
  *     Exactly one page per row per call.  scores: [S][Hk][max_blocks] fp32 (e.g. from (1)); compared
  *     as fp32 values.  block_table and seq_lens are updated in place.
+ *     shared: the sequence's one table row [S][max_blocks] drops the page with the lowest head-mean score
+ *     (scores stays [S][Hk][max_blocks]); evicted_logical_out / freed_phys_out are [S].  The same holds for
+ *     the variants below (share_heads is then implied).
  */
 int pe_evict_blocks(const pe_cache_desc* desc, const float* scores, int32_t* block_table, int32_t* seq_lens,
                     int32_t budget_tokens, int32_t* evicted_logical_out, int32_t* freed_phys_out, void* stream);
@@ -201,6 +221,7 @@ int pe_evict_blocks_ex(const pe_cache_desc* desc, const pe_evict_opts* opts, flo
  *     row (s, h / (Hq/Hk)), token t being slot t % B of page block_table[s][hk][t / B].
  *     fp32 accumulation, output rounded to desc->dtype.  seq_lens[s] == 0 gives zeros.
  *     q, out: [S][Hq][D].  workspace: pe_workspace_bytes(PE_OP_PAGED_DECODE, desc, 0) (split partials).
+ *     shared: block_table [S][max_blocks]; query head h reads head h/(Hq/Hk) of the sequence's pages.
  */
 int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool, const void* v_pool,
                     const int32_t* block_table, const int32_t* seq_lens, float softmax_scale, void* out,
@@ -214,6 +235,7 @@ int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool
  * spare[s][hk][spare_used[s][hk]++].  Then seq_lens[s] += 1.
  * new_k, new_v: [S][Hk][D].  spare: [S][Hk][n_spare] int32.  spare_used, freed_phys: [S][Hk] int32,
  * updated in place.  Preconditions: seq_lens[s] < max_blocks*B; the spare list is not exhausted.
+ * shared: one page per sequence takes the rows of all heads; spare [S][n_spare], spare_used and freed_phys [S].
  */
 int pe_append_kv(const pe_cache_desc* desc, const void* new_k, const void* new_v, void* k_pool, void* v_pool,
                  int32_t* block_table, int32_t* seq_lens, int32_t* freed_phys, const int32_t* spare,

@@ -30,7 +30,7 @@ EXPORTS = ["pe_workspace_bytes", "pe_status_string", "pe_version", "pe_set_optio
 class pe_cache_desc(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("num_seqs", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
                 ("num_q_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32),
-                ("max_blocks", ctypes.c_int32), ("num_phys_blocks", ctypes.c_int64)]
+                ("max_blocks", ctypes.c_int32), ("num_phys_blocks", ctypes.c_int64), ("layout", ctypes.c_int32)]
 
 
 class pe_evict_opts(ctypes.Structure):
@@ -39,6 +39,7 @@ class pe_evict_opts(ctypes.Structure):
 
 
 PE_POLICY_LOWEST_SCORE, PE_POLICY_OLDEST = 0, 1
+PE_LAYOUT_PER_HEAD, PE_LAYOUT_SHARED = 0, 1
 
 
 class PeError(RuntimeError):
@@ -111,10 +112,11 @@ def pe_get_option(key: int) -> int:
     return int(lib().pe_get_option(int(key)))
 
 
-def make_desc(dtype, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, max_blocks, num_phys_blocks):
+def make_desc(dtype, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, max_blocks, num_phys_blocks,
+              layout=0):
     code = {torch.float32: PE_F32, torch.bfloat16: PE_BF16}.get(dtype, dtype if isinstance(dtype, int) else -1)
     return pe_cache_desc(int(code), int(num_seqs), int(num_kv_heads), int(num_q_heads), int(head_dim),
-                         int(block_size), int(max_blocks), int(num_phys_blocks))
+                         int(block_size), int(max_blocks), int(num_phys_blocks), int(layout))
 
 
 def _check(status, where):
@@ -312,23 +314,38 @@ class PagedCache:
 
     @staticmethod
     def create(dtype, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, layout, budget, device="cuda",
-               k_pool=None, v_pool=None):
+               k_pool=None, v_pool=None, shared=False):
+        """`layout`: block table, spare lists and pool size (synth.page_layout).  shared=True builds the
+        head-shared cache (PE_LAYOUT_SHARED): `layout` then describes ONE row per sequence (a layout made for a
+        single KV head), pools are [P, B, Hk, D] and the per-row arrays lose their head dimension."""
         desc = make_desc(dtype, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, layout.max_blocks,
-                         layout.num_phys_blocks)
-        shape = (layout.num_phys_blocks, block_size, head_dim)
+                         layout.num_phys_blocks, PE_LAYOUT_SHARED if shared else PE_LAYOUT_PER_HEAD)
+        table, spare = layout.block_table, layout.spare
+        if shared:
+            assert table.shape[1] == 1, "a shared cache takes a layout with one row per sequence"
+            table, spare = table[:, 0], spare[:, 0]
+            shape = (layout.num_phys_blocks, block_size, num_kv_heads, head_dim)
+            per_row = (num_seqs,)
+        else:
+            shape = (layout.num_phys_blocks, block_size, head_dim)
+            per_row = (num_seqs, num_kv_heads)
         if k_pool is None:
             k_pool = torch.zeros(shape, dtype=dtype, device=device)
             v_pool = torch.zeros(shape, dtype=dtype, device=device)
         i32 = dict(dtype=torch.int32, device=device)
-        cache = PagedCache(desc, k_pool, v_pool, layout.block_table.to(device).contiguous(),
-                           torch.zeros(num_seqs, **i32), layout.spare.to(device).contiguous(),
-                           torch.zeros((num_seqs, num_kv_heads), **i32), torch.full((num_seqs, num_kv_heads), -1, **i32),
-                           torch.full((num_seqs, num_kv_heads), -1, **i32),
+        cache = PagedCache(desc, k_pool, v_pool, table.to(device).contiguous(),
+                           torch.zeros(num_seqs, **i32), spare.to(device).contiguous(),
+                           torch.zeros(per_row, **i32), torch.full(per_row, -1, **i32),
+                           torch.full(per_row, -1, **i32),
                            torch.empty((num_seqs, num_kv_heads, layout.max_blocks), dtype=torch.float32, device=device),
                            int(budget))
         cache.decode_ws = alloc_workspace(PE_OP_PAGED_DECODE, desc, device=device)
         cache.host_lens = [0] * num_seqs
         return cache
+
+    @property
+    def shared(self) -> bool:
+        return self.desc.layout == PE_LAYOUT_SHARED
 
     def prefill_prune(self, k_in, v_in, cu_seqlens, max_seqlen, kept_idx_out=None, workspace=None):
         total = k_in.shape[0]
@@ -363,7 +380,7 @@ class PagedCache:
         if self.any_trigger():
             self.score_and_evict()
             self.host_lens = [n - B if (n > 0 and n % B == 0 and n >= self.budget) else n for n in self.host_lens]
-        if fused:
+        if fused and not self.shared:   # the one-launch append + attention exists for the per-head layout only
             self.append_paged_decode(new_k, new_v, q, out, softmax_scale)
         else:
             self.append_kv(new_k, new_v)

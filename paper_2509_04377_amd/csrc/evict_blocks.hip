@@ -36,7 +36,7 @@ __global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* sco
                                                                 int32_t* __restrict__ freed_phys, int num_kv_heads,
                                                                 int block_size, int max_blocks, int budget,
                                                                 int policy, int protect_first, int protect_last,
-                                                                int share_heads) {
+                                                                int share_heads, int shared) {
   const int s = (int)blockIdx.x;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
@@ -72,6 +72,29 @@ __global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* sco
     j_shared = __builtin_amdgcn_readfirstlane(best_j);
   }
   if (share_heads) __syncthreads();
+
+  if (shared) {
+    // one table row per sequence: wave 0 moves it (and score row 0), the other waves only their score rows
+    for (int h = wave; h < num_kv_heads; h += kWaves) {
+      if (!trigger) {
+        if (h == 0 && lane == 0) {
+          evicted_logical[s] = -1;
+          freed_phys[s] = -1;
+        }
+        continue;
+      }
+      float* sc_mut = scores_mut != nullptr ? scores_mut + ((int64_t)s * num_kv_heads + h) * max_blocks : nullptr;
+      int32_t* bt = h == 0 ? block_table + (int64_t)s * max_blocks : nullptr;
+      const int freed = compact_row(bt, sc_mut, j_shared, n, lane);
+      if (h == 0 && lane == 0) {
+        evicted_logical[s] = j_shared;
+        freed_phys[s] = freed;
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && trigger) seq_lens[s] = len - block_size;
+    return;
+  }
 
   for (int h = wave; h < num_kv_heads; h += kWaves) {
     const int64_t row = (int64_t)s * num_kv_heads + h;
@@ -116,7 +139,6 @@ __global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* sco
 
 // Append: one workgroup per sequence.  Phase 1 links a new page into each row when the tail page is
 // full; phase 2 copies the new K/V rows with 16-byte lane accesses.
-template <int VEC_PER_ROW>
 __global__ __launch_bounds__(kThreads) void append_kv_kernel(const uint4* __restrict__ new_k,
                                                              const uint4* __restrict__ new_v,
                                                              uint4* __restrict__ k_pool, uint4* __restrict__ v_pool,
@@ -125,7 +147,8 @@ __global__ __launch_bounds__(kThreads) void append_kv_kernel(const uint4* __rest
                                                              int32_t* __restrict__ freed_phys,
                                                              const int32_t* __restrict__ spare,
                                                              int32_t* __restrict__ spare_used, int n_spare,
-                                                             int num_kv_heads, int block_size, int max_blocks) {
+                                                             int num_kv_heads, int block_size, int max_blocks,
+                                                             int VEC_PER_ROW) {
   const int s = (int)blockIdx.x;
   const int len = seq_lens[s];
   const int slot = len % block_size;
@@ -164,25 +187,21 @@ __global__ __launch_bounds__(kThreads) void append_kv_kernel(const uint4* __rest
 hipError_t launch_evict_blocks(const EvictArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL(evict_blocks_kernel, dim3((unsigned)a.num_seqs), dim3(kThreads), 0, stream, a.scores,
                      a.scores_mut, a.block_table, a.seq_lens, a.evicted_logical, a.freed_phys, a.num_kv_heads, a.block_size,
-                     a.max_blocks, a.budget, a.policy, a.protect_first, a.protect_last, a.share_heads);
+                     a.max_blocks, a.budget, a.policy, a.protect_first, a.protect_last, (a.share_heads || a.shared) ? 1 : 0,
+                     a.shared ? 1 : 0);
   return hipGetLastError();
 }
 
 hipError_t launch_append_kv(const AppendArgs& a, hipStream_t stream) {
-  const int vec_per_row = a.head_dim * (a.is_bf16 ? 2 : 4) / 16;
-#define PE_APPEND(V)                                                                                          \
-  if (vec_per_row == V) {                                                                                     \
-    hipLaunchKernelGGL((append_kv_kernel<V>), dim3((unsigned)a.num_seqs), dim3(kThreads), 0, stream,          \
-                       (const uint4*)a.new_k, (const uint4*)a.new_v, (uint4*)a.k_pool, (uint4*)a.v_pool,      \
-                       a.block_table, a.seq_lens, a.freed_phys, a.spare, a.spare_used, a.n_spare,             \
-                       a.num_kv_heads, a.block_size, a.max_blocks);                                           \
-    return hipGetLastError();                                                                                 \
-  }
-  PE_APPEND(8)
-  PE_APPEND(16)
-  PE_APPEND(32)
-#undef PE_APPEND
-  return hipErrorInvalidValue;
+  const int vec_per_head_row = a.head_dim * (a.is_bf16 ? 2 : 4) / 16;
+  // shared: the sequence is one row of Hk * D elements with one table row, spare list and freed page
+  const int rows_per_seq = a.shared ? 1 : a.num_kv_heads;
+  const int vec_per_row = a.shared ? vec_per_head_row * a.num_kv_heads : vec_per_head_row;
+  hipLaunchKernelGGL(append_kv_kernel, dim3((unsigned)a.num_seqs), dim3(kThreads), 0, stream, (const uint4*)a.new_k,
+                     (const uint4*)a.new_v, (uint4*)a.k_pool, (uint4*)a.v_pool, a.block_table, a.seq_lens,
+                     a.freed_phys, a.spare, a.spare_used, a.n_spare, rows_per_seq, a.block_size, a.max_blocks,
+                     vec_per_row);
+  return hipGetLastError();
 }
 
 }  // namespace pe

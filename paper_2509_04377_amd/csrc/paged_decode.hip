@@ -196,7 +196,8 @@ struct Tile {
   // unconditional, which keeps the order of outstanding loads known at compile time, so waiting for the
   // oldest tile leaves the younger ones in flight.
   static __device__ __forceinline__ void issue(uint4 (&kb)[NLT], uint4 (&vb)[NLT], int tile, const int (&phys)[NPT],
-                                               const T* k_pool, const T* v_pool, int log2_block, int lane_off) {
+                                               const T* k_pool, const T* v_pool, int log2_block, int lane_off,
+                                               int row_vecs = LPR) {
     const int tok0 = tile * TT;
 #pragma unroll
     for (int i = 0; i < NLT; ++i) {
@@ -206,7 +207,7 @@ struct Tile {
       for (int e = 1; e < NPT; ++e)
         if (((i * TPL) >> log2_block) == e) ph = phys[e];
       const int slot0 = t & ((1 << log2_block) - 1);
-      const int64_t vec = (((int64_t)ph << log2_block) + slot0) * LPR + lane_off;
+      const int64_t vec = (((int64_t)ph << log2_block) + slot0) * row_vecs + lane_off;
       kb[i] = load_vec_stream(k_pool, vec);
       vb[i] = load_vec_stream(v_pool, vec);
     }
@@ -261,8 +262,9 @@ struct Tile {
   }
 };
 
-template <typename T, int D, int G, int WAVES, int DEPTH, int LOADS, bool FUSED>
+template <typename T, int D, int G, int WAVES, int DEPTH, int LOADS, bool FUSED, bool SHARED = false>
 __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const DecodeParams p) {
+  static_assert(!(FUSED && SHARED), "the fused append is per-head only");
   using TL = Tile<T, D, G, LOADS>;
   constexpr int EPL = TL::EPL, LPR = TL::LPR, TPL = TL::TPL, NLT = TL::NLT, TT = TL::TT, GP = TL::GP;
   constexpr int GBITS = ilog2(GP);
@@ -294,7 +296,11 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
   }
   const int s = row / p.num_kv_heads;
   const int hk = row % p.num_kv_heads;
-  const int32_t* bt = p.block_table + (int64_t)row * p.max_blocks;
+  // SHARED: one table row per sequence; a page holds [B][Hk][D], so consecutive tokens of this head are
+  // Hk rows apart and a lane's offset inside a wave-load carries the head
+  const int32_t* bt = p.block_table + (int64_t)(SHARED ? s : row) * p.max_blocks;
+  const int row_vecs = SHARED ? LPR * p.num_kv_heads : LPR;
+  const int lane_vec = SHARED ? (grp * p.num_kv_heads + hk) * LPR + u : lane;
   const T* k_pool = static_cast<const T*>(p.k_pool);
   const T* v_pool = static_cast<const T*>(p.v_pool);
 
@@ -353,7 +359,7 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
     if (p.splits != 1) TL::lookup(phys, first, bt, p.max_blocks, p.log2_block);
 #pragma unroll
     for (int d = 0; d < DEPTH - 1; ++d) {
-      TL::issue(kb[d], vb[d], tile_at(d), phys, k_pool, v_pool, p.log2_block, d < n_mine ? lane : 0);
+      TL::issue(kb[d], vb[d], tile_at(d), phys, k_pool, v_pool, p.log2_block, d < n_mine ? lane_vec : 0, row_vecs);
       TL::lookup(phys, tile_at(d + 1), bt, p.max_blocks, p.log2_block);
     }
     for (int i = 0; i < n_mine; i += DEPTH) {
@@ -361,7 +367,7 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
       for (int ph = 0; ph < DEPTH; ++ph) {
         const int ahead = i + ph + DEPTH - 1;
         TL::issue(kb[(ph + DEPTH - 1) % DEPTH], vb[(ph + DEPTH - 1) % DEPTH], tile_at(ahead), phys, k_pool, v_pool,
-                  p.log2_block, ahead < n_mine ? lane : 0);
+                  p.log2_block, ahead < n_mine ? lane_vec : 0, row_vecs);
         TL::lookup(phys, tile_at(ahead + 1), bt, p.max_blocks, p.log2_block);
         if (i + ph < n_mine) {
           TL::template compute<NLT>(kb[ph], vb[ph], (first + (i + ph) * WAVES) * TT, len_pool, grp, p.scale_log2e, qs,
@@ -536,7 +542,15 @@ hipError_t launch_one(const DecodeArgs& a, hipStream_t stream) {
   p.xcd_map = (a.xcd_map && rows % 8 == 0) ? 1 : 0;
   const int64_t grid = rows * a.splits;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  if (a.new_k != nullptr) {
+  if (a.shared) {
+    if (a.new_k != nullptr) return hipErrorInvalidValue;
+    if constexpr (WAVES == 4 && DEPTH == 2 && LOADS == 2) {
+      hipLaunchKernelGGL((paged_decode_kernel<T, D, G, WAVES, DEPTH, LOADS, false, true>), dim3((unsigned)grid),
+                         dim3(WAVES * kWave), 0, stream, p);
+    } else {
+      return hipErrorInvalidValue;
+    }
+  } else if (a.new_k != nullptr) {
     hipLaunchKernelGGL((paged_decode_kernel<T, D, G, WAVES, DEPTH, LOADS, true>), dim3((unsigned)grid), dim3(WAVES * kWave), 0,
                        stream, p);
   } else {

@@ -22,6 +22,7 @@ int check_desc(const pe_cache_desc* d) {
   if (d->head_dim != 64 && d->head_dim != 128) return PE_ERR_UNSUPPORTED;
   if (d->block_size != 16 && d->block_size != 32 && d->block_size != 64 && d->block_size != 128)
     return PE_ERR_UNSUPPORTED;
+  if (d->layout != PE_LAYOUT_PER_HEAD && d->layout != PE_LAYOUT_SHARED) return PE_ERR_UNSUPPORTED;
   if (d->num_phys_blocks > 0x7fffffffLL) return PE_ERR_UNSUPPORTED;
   if ((int64_t)d->num_seqs * d->num_kv_heads > 0x7fffffffLL / 64) return PE_ERR_UNSUPPORTED;
   return PE_OK;
@@ -92,7 +93,8 @@ size_t pe_workspace_bytes(int op, const pe_cache_desc* desc, int64_t total_token
       return pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, decode_splits(desc));
     case PE_OP_PREFILL_PRUNE:
       if (total_tokens < 0) return 0;
-      return pe::prune_workspace_bytes(desc->num_seqs, desc->num_kv_heads, total_tokens);
+      return pe::prune_workspace_bytes(desc->num_seqs, desc->num_kv_heads, total_tokens,
+                                       desc->layout == PE_LAYOUT_SHARED);
     default:
       return 0;
   }
@@ -137,6 +139,7 @@ int score_blocks_impl(const pe_cache_desc* desc, const void* k_pool, const void*
   a.block_size = desc->block_size;
   a.max_blocks = desc->max_blocks;
   a.is_bf16 = desc->dtype == PE_BF16;
+  a.shared = desc->layout == PE_LAYOUT_SHARED;
   a.recent = recent;
   return pe::launch_score_blocks(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
@@ -156,7 +159,8 @@ int pe_prefill_prune(const pe_cache_desc* desc, const void* k_in, const void* v_
   if (!aligned(k_pool, 16) || !aligned(v_pool, 16) || !aligned(k_in, 16) || !aligned(v_in, 16))
     return PE_ERR_INVALID_ARG;
   const int ws = check_workspace(workspace, workspace_bytes,
-                                 pe::prune_workspace_bytes(desc->num_seqs, desc->num_kv_heads, total_tokens));
+                                 pe::prune_workspace_bytes(desc->num_seqs, desc->num_kv_heads, total_tokens,
+                                                           desc->layout == PE_LAYOUT_SHARED));
   if (ws != PE_OK) return ws;
   pe::PruneArgs a;
   a.k_in = k_in;
@@ -177,6 +181,7 @@ int pe_prefill_prune(const pe_cache_desc* desc, const void* k_in, const void* v_
   a.block_size = desc->block_size;
   a.max_blocks = desc->max_blocks;
   a.is_bf16 = desc->dtype == PE_BF16;
+  a.shared = desc->layout == PE_LAYOUT_SHARED;
   return pe::launch_prefill_prune(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
 
@@ -207,6 +212,7 @@ int pe_score_evict(const pe_cache_desc* desc, const void* k_pool, const void* v_
     return PE_ERR_INVALID_ARG;
   if (!aligned(k_pool, 16) || !aligned(v_pool, 16)) return PE_ERR_INVALID_ARG;
   if (budget_tokens <= 0 || budget_tokens % desc->block_size != 0) return PE_ERR_INVALID_ARG;
+  if (desc->layout != PE_LAYOUT_PER_HEAD) return PE_ERR_UNSUPPORTED;  // needs every head's score before the argmin
   pe::ScoreEvictArgs a;
   a.k_pool = k_pool;
   a.v_pool = v_pool;
@@ -258,6 +264,7 @@ int evict_blocks_impl(const pe_cache_desc* desc, const float* scores, float* sco
   a.block_size = desc->block_size;
   a.max_blocks = desc->max_blocks;
   a.budget = budget_tokens;
+  a.shared = desc->layout == PE_LAYOUT_SHARED;
   if (opts != nullptr) {
     a.policy = opts->policy;
     a.protect_first = opts->protect_first;
@@ -302,6 +309,7 @@ int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool
   a.depth = g_options[PE_OPT_DECODE_DEPTH];
   a.loads = g_options[PE_OPT_DECODE_LOADS];
   a.is_bf16 = desc->dtype == PE_BF16;
+  a.shared = desc->layout == PE_LAYOUT_SHARED;
   return pe::launch_paged_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
 
@@ -317,6 +325,8 @@ int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const v
     return PE_ERR_INVALID_ARG;
   if (seq_lens_out == seq_lens) return PE_ERR_INVALID_ARG;
   if (n_spare < 1) return PE_ERR_INVALID_ARG;
+  // the heads of a sequence run in different workgroups and would race on the sequence's one table row
+  if (desc->layout != PE_LAYOUT_PER_HEAD) return PE_ERR_UNSUPPORTED;
   if (!aligned(k_pool, 16) || !aligned(v_pool, 16) || !aligned(q, 16) || !aligned(new_k, 16) || !aligned(new_v, 16))
     return PE_ERR_INVALID_ARG;
   if (!(softmax_scale == softmax_scale) || softmax_scale - softmax_scale != 0.f) return PE_ERR_INVALID_ARG;
@@ -346,6 +356,7 @@ int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const v
   a.depth = g_options[PE_OPT_DECODE_DEPTH];
   a.loads = g_options[PE_OPT_DECODE_LOADS];
   a.is_bf16 = desc->dtype == PE_BF16;
+  a.shared = desc->layout == PE_LAYOUT_SHARED;
   a.new_k = new_k;
   a.new_v = new_v;
   a.freed_phys = freed_phys;
@@ -383,6 +394,7 @@ int pe_append_kv(const pe_cache_desc* desc, const void* new_k, const void* new_v
   a.block_size = desc->block_size;
   a.max_blocks = desc->max_blocks;
   a.is_bf16 = desc->dtype == PE_BF16;
+  a.shared = desc->layout == PE_LAYOUT_SHARED;
   return pe::launch_append_kv(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
 

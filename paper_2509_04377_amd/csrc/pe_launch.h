@@ -17,6 +17,7 @@ struct ScoreArgs {
   int num_seqs, num_kv_heads, head_dim, block_size, max_blocks;
   bool is_bf16;
   int recent = 0;  // 0: score every page; n > 0: only the n most recently filled pages of each row
+  bool shared = false;  // one table row per sequence, pages [B][Hk][D]
 };
 hipError_t launch_score_blocks(const ScoreArgs& a, hipStream_t stream);
 
@@ -42,6 +43,7 @@ struct EvictArgs {
   int32_t* freed_phys;
   int num_seqs, num_kv_heads, block_size, max_blocks, budget;
   int policy = 0, protect_first = 0, protect_last = 0, share_heads = 0;
+  bool shared = false;  // one table row per sequence (implies share_heads); outputs are [S]
 };
 hipError_t launch_evict_blocks(const EvictArgs& a, hipStream_t stream);
 
@@ -57,6 +59,7 @@ struct AppendArgs {
   int32_t* spare_used;
   int n_spare, num_seqs, num_kv_heads, head_dim, block_size, max_blocks;
   bool is_bf16;
+  bool shared = false;  // one table row, one spare list and one freed page per sequence
 };
 hipError_t launch_append_kv(const AppendArgs& a, hipStream_t stream);
 
@@ -83,6 +86,7 @@ struct DecodeArgs {
   int32_t* spare_used = nullptr;
   int32_t* seq_lens_out = nullptr;
   int n_spare = 0;
+  bool shared = false;  // one table row per sequence, pages [B][Hk][D]; plain attention only
 };
 hipError_t launch_paged_decode(const DecodeArgs& a, hipStream_t stream);
 size_t decode_partials_bytes(int num_seqs, int num_q_heads, int head_dim, int splits);
@@ -101,8 +105,9 @@ struct PruneArgs {
   int max_seqlen, budget;
   int num_seqs, num_kv_heads, head_dim, block_size, max_blocks;
   bool is_bf16;
+  bool shared = false;  // one decision per sequence (head-mean token scores), pages [B][Hk][D]
 };
 hipError_t launch_prefill_prune(const PruneArgs& a, hipStream_t stream);
-size_t prune_workspace_bytes(int num_seqs, int num_kv_heads, int64_t total_tokens);
+size_t prune_workspace_bytes(int num_seqs, int num_kv_heads, int64_t total_tokens, bool shared);
 
 }  // namespace pe

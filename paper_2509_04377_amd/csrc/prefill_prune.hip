@@ -12,6 +12,10 @@
 //   4. gather:        per row and chunk, an index-ordered scan turns those counts into the destination
 //                     of every kept token; token rows are then copied with 16-byte lane accesses.
 // A token is kept iff score > T, or score == T and at least q equal-score tokens precede it.
+//
+// Head-shared mode (one decision per sequence, pages [B][Hk][D]): after kernel 1 the per-head scores are
+// averaged over the heads (head order, fp64, one rounding) into one more score row, and kernels 2-4 run on
+// that row with the whole (token, all heads) record as the unit that is copied.
 #include "pe_device.h"
 #include "pe_launch.h"
 #include "pe_norms.h"
@@ -27,7 +31,7 @@ constexpr int kTokPerThread = kChunk / kThreads;
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {
-  float* scores;  // [Hk][total_tokens]
+  float* scores;  // [Hk][total_tokens]; shared mode: one more row, the mean over heads
   uint32_t* sel;  // [rows][2]: threshold bits T, tie quota q
   int32_t* cnt;   // [Hk][chunk_slots][2]: (#score > T, #score == T) per chunk
   int64_t chunk_slots;
@@ -37,11 +41,11 @@ __host__ inline int64_t chunk_slots_for(int64_t total_tokens, int num_seqs) {
   return total_tokens / kChunk + num_seqs + 1;
 }
 
-__host__ inline Workspace carve(void* base, int num_seqs, int num_kv_heads, int64_t total_tokens) {
+__host__ inline Workspace carve(void* base, int num_seqs, int num_kv_heads, int64_t total_tokens, bool shared) {
   Workspace w;
   char* p = static_cast<char*>(base);
   w.scores = reinterpret_cast<float*>(p);
-  p += align256(sizeof(float) * (size_t)num_kv_heads * (size_t)total_tokens);
+  p += align256(sizeof(float) * (size_t)(num_kv_heads + (shared ? 1 : 0)) * (size_t)total_tokens);
   w.sel = reinterpret_cast<uint32_t*>(p);
   p += align256(sizeof(uint32_t) * 2 * (size_t)num_seqs * num_kv_heads);
   w.cnt = reinterpret_cast<int32_t*>(p);
@@ -113,6 +117,17 @@ __global__ __launch_bounds__(kThreads) void token_scores_kernel(const T* __restr
       }
     }
   }
+}
+
+// ---- 1b. head-shared mode: mean over heads of the fp32 token scores -----------------------------------
+__global__ __launch_bounds__(kThreads) void head_mean_kernel(const float* __restrict__ scores,
+                                                             float* __restrict__ mean_out, int64_t total_tokens,
+                                                             int num_kv_heads) {
+  const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (t >= total_tokens) return;
+  double sum = 0.0;
+  for (int h = 0; h < num_kv_heads; ++h) sum += (double)scores[(int64_t)h * total_tokens + t];
+  mean_out[t] = (float)(sum / (double)num_kv_heads);
 }
 
 // ---- 2. per-row radix select ------------------------------------------------------------------------
@@ -254,7 +269,9 @@ __global__ __launch_bounds__(kThreads) void chunk_counts_kernel(const float* __r
 }
 
 // ---- 4. gather ----------------------------------------------------------------------------------------
-template <int VEC_PER_ROW>
+// VPR_T > 0: vectors per token row known at compile time; 0: taken from vpr_rt (head-shared mode, where a
+// row is the K (or V) of all heads of a token).
+template <int VPR_T>
 __global__ __launch_bounds__(kThreads) void gather_kernel(const uint4* __restrict__ k_in, const uint4* __restrict__ v_in,
                                                           const float* __restrict__ scores,
                                                           const int32_t* __restrict__ cu_seqlens,
@@ -264,7 +281,7 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(const uint4* __restric
                                                           uint4* __restrict__ k_pool, uint4* __restrict__ v_pool,
                                                           int32_t* __restrict__ kept_idx_out, int64_t total_tokens,
                                                           int64_t chunk_slots, int num_kv_heads, int chunks_per_row,
-                                                          int block_size, int max_blocks, int budget) {
+                                                          int block_size, int max_blocks, int budget, int vpr_rt) {
   __shared__ int sh[kWaves];
   __shared__ int wave_off[kWaves][2];
   __shared__ int32_t src_tok[kChunk];  // kept tokens of this chunk: in-sequence index
@@ -350,14 +367,28 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(const uint4* __restric
 
   // copy the kept rows: VEC_PER_ROW lanes per token row, K and V
   const int32_t* bt = block_table + (int64_t)row * max_blocks;
-  constexpr int kRowsPerPass = kThreads / VEC_PER_ROW;
-  const int u = tid % VEC_PER_ROW, r = tid / VEC_PER_ROW;
-  for (int base = 0; base < n_kept; base += kRowsPerPass) {
-    const int e = base + r;
-    if (e < n_kept) {
+  if constexpr (VPR_T > 0) {
+    constexpr int VEC_PER_ROW = VPR_T;
+    constexpr int kRowsPerPass = kThreads / VEC_PER_ROW;
+    const int u = tid % VEC_PER_ROW, r = tid / VEC_PER_ROW;
+    for (int base = 0; base < n_kept; base += kRowsPerPass) {
+      const int e = base + r;
+      if (e < n_kept) {
+        const int tok = src_tok[e], pos = dst_pos[e];
+        const int64_t src = ((int64_t)(t0 + tok) * num_kv_heads + h) * VEC_PER_ROW + u;
+        const int64_t dst = ((int64_t)bt[pos / block_size] * block_size + pos % block_size) * VEC_PER_ROW + u;
+        k_pool[dst] = k_in[src];
+        v_pool[dst] = v_in[src];
+        if (kept_idx_out != nullptr && u == 0) kept_idx_out[(int64_t)row * budget + pos] = tok;
+      }
+    }
+  } else {
+    const int total_vecs = n_kept * vpr_rt;
+    for (int f = tid; f < total_vecs; f += kThreads) {
+      const int e = f / vpr_rt, u = f - e * vpr_rt;
       const int tok = src_tok[e], pos = dst_pos[e];
-      const int64_t src = ((int64_t)(t0 + tok) * num_kv_heads + h) * VEC_PER_ROW + u;
-      const int64_t dst = ((int64_t)bt[pos / block_size] * block_size + pos % block_size) * VEC_PER_ROW + u;
+      const int64_t src = ((int64_t)(t0 + tok) * num_kv_heads + h) * vpr_rt + u;
+      const int64_t dst = ((int64_t)bt[pos / block_size] * block_size + pos % block_size) * vpr_rt + u;
       k_pool[dst] = k_in[src];
       v_pool[dst] = v_in[src];
       if (kept_idx_out != nullptr && u == 0) kept_idx_out[(int64_t)row * budget + pos] = tok;
@@ -368,8 +399,7 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(const uint4* __restric
 template <typename T, int D>
 hipError_t launch(const PruneArgs& a, hipStream_t stream) {
   using G = RowGeom<T, D>;
-  const Workspace w = carve(a.workspace, a.num_seqs, a.num_kv_heads, a.total_tokens);
-  const int rows = a.num_seqs * a.num_kv_heads;
+  const Workspace w = carve(a.workspace, a.num_seqs, a.num_kv_heads, a.total_tokens, a.shared);
   const int64_t total_rows = a.total_tokens * a.num_kv_heads;
   hipError_t e;
   if (total_rows > 0) {
@@ -380,28 +410,50 @@ hipError_t launch(const PruneArgs& a, hipStream_t stream) {
                        (const T*)a.k_in, (const T*)a.v_in, w.scores, total_rows, a.total_tokens, a.num_kv_heads);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(select_kernel, dim3((unsigned)rows), dim3(kSelThreads), 0, stream, w.scores, a.cu_seqlens, w.sel,
-                     a.seq_lens_out, a.kept_idx_out, a.total_tokens, a.num_kv_heads, a.budget);
+  // what kernels 2-4 see: per-head rows, or (shared) one row per sequence whose score is the head mean and
+  // whose record is the token's K (or V) of all heads
+  const int heads = a.shared ? 1 : a.num_kv_heads;
+  const float* sel_scores = w.scores;
+  if (a.shared) {
+    float* mean = w.scores + (size_t)a.num_kv_heads * (size_t)a.total_tokens;
+    if (a.total_tokens > 0) {
+      const int64_t grid = (a.total_tokens + kThreads - 1) / kThreads;
+      hipLaunchKernelGGL(head_mean_kernel, dim3((unsigned)grid), dim3(kThreads), 0, stream, w.scores, mean,
+                         a.total_tokens, a.num_kv_heads);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    sel_scores = mean;
+  }
+  const int rows = a.num_seqs * heads;
+  hipLaunchKernelGGL(select_kernel, dim3((unsigned)rows), dim3(kSelThreads), 0, stream, sel_scores, a.cu_seqlens,
+                     w.sel, a.seq_lens_out, a.kept_idx_out, a.total_tokens, heads, a.budget);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const int chunks_per_row = (a.max_seqlen + kChunk - 1) / kChunk;
   if (chunks_per_row == 0) return hipSuccess;
   const int64_t grid2 = (int64_t)rows * chunks_per_row;
   if (grid2 > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(chunk_counts_kernel, dim3((unsigned)grid2), dim3(kThreads), 0, stream, w.scores, a.cu_seqlens,
-                     w.sel, w.cnt, a.total_tokens, w.chunk_slots, a.num_kv_heads, chunks_per_row);
+  hipLaunchKernelGGL(chunk_counts_kernel, dim3((unsigned)grid2), dim3(kThreads), 0, stream, sel_scores, a.cu_seqlens,
+                     w.sel, w.cnt, a.total_tokens, w.chunk_slots, heads, chunks_per_row);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   constexpr int VPR = G::kLanesPerRow;
-  hipLaunchKernelGGL((gather_kernel<VPR>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, (const uint4*)a.k_in,
-                     (const uint4*)a.v_in, w.scores, a.cu_seqlens, w.sel, w.cnt, a.block_table, (uint4*)a.k_pool,
-                     (uint4*)a.v_pool, a.kept_idx_out, a.total_tokens, w.chunk_slots, a.num_kv_heads, chunks_per_row,
-                     a.block_size, a.max_blocks, a.budget);
+  if (a.shared) {
+    hipLaunchKernelGGL((gather_kernel<0>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, (const uint4*)a.k_in,
+                       (const uint4*)a.v_in, sel_scores, a.cu_seqlens, w.sel, w.cnt, a.block_table, (uint4*)a.k_pool,
+                       (uint4*)a.v_pool, a.kept_idx_out, a.total_tokens, w.chunk_slots, heads, chunks_per_row,
+                       a.block_size, a.max_blocks, a.budget, VPR * a.num_kv_heads);
+  } else {
+    hipLaunchKernelGGL((gather_kernel<VPR>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, (const uint4*)a.k_in,
+                       (const uint4*)a.v_in, sel_scores, a.cu_seqlens, w.sel, w.cnt, a.block_table, (uint4*)a.k_pool,
+                       (uint4*)a.v_pool, a.kept_idx_out, a.total_tokens, w.chunk_slots, heads, chunks_per_row,
+                       a.block_size, a.max_blocks, a.budget, VPR);
+  }
   return hipGetLastError();
 }
 
 }  // namespace
 
-size_t prune_workspace_bytes(int num_seqs, int num_kv_heads, int64_t total_tokens) {
-  return align256(sizeof(float) * (size_t)num_kv_heads * (size_t)total_tokens) +
+size_t prune_workspace_bytes(int num_seqs, int num_kv_heads, int64_t total_tokens, bool shared) {
+  return align256(sizeof(float) * (size_t)(num_kv_heads + (shared ? 1 : 0)) * (size_t)total_tokens) +
          align256(sizeof(uint32_t) * 2 * (size_t)num_seqs * num_kv_heads) +
          align256(sizeof(int32_t) * 2 * (size_t)num_kv_heads * (size_t)chunk_slots_for(total_tokens, num_seqs));
 }

@@ -31,14 +31,15 @@ struct ChunkScore {
   static_assert(NV <= LPR, "reduce-scatter needs at least as many lanes per row as values");
   static constexpr int kVecPerChunk = CH * D / G::kPerVec;
 
-  // vec_base: index (in 16-byte units) of the chunk's first element
+  // vec_base: index (in 16-byte units) of the chunk's first element; lane_vec: this lane's offset inside a
+  // wave-load (the lane id when token rows are contiguous); load_stride: distance between wave-loads
   static __device__ __forceinline__ void issue(uint4 (&kb)[NL], uint4 (&vb)[NL], const T* k_pool, const T* v_pool,
-                                               int64_t vec_base, int lane) {
-    const int64_t base = vec_base + lane;
+                                               int64_t vec_base, int lane_vec, int load_stride = kWave) {
+    const int64_t base = vec_base + lane_vec;
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-      kb[i] = load_vec_stream(k_pool, base + i * kWave);
-      vb[i] = load_vec_stream(v_pool, base + i * kWave);
+      kb[i] = load_vec_stream(k_pool, base + (int64_t)i * load_stride);
+      vb[i] = load_vec_stream(v_pool, base + (int64_t)i * load_stride);
     }
   }
 
@@ -85,7 +86,8 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
                                                                 const int32_t* __restrict__ block_table,
                                                                 const int32_t* __restrict__ seq_lens,
                                                                 float* __restrict__ scores, int num_kv_heads,
-                                                                int max_blocks, int groups_per_row, int recent) {
+                                                                int max_blocks, int groups_per_row, int recent,
+                                                                int shared) {
   using PG = PageGeom<T, D, B>;
   using CS = typename PG::CS;
   constexpr int NL = CS::NL;
@@ -99,7 +101,12 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
   const int s = row / num_kv_heads;
   const int nfull_raw = seq_lens[s] / B;
   const int nfull = nfull_raw < max_blocks ? nfull_raw : max_blocks;  // never index past the table row
-  const int32_t* bt = block_table + (int64_t)row * max_blocks;
+  // shared: one table row per sequence and pages of [B][Hk][D]: the token rows of this head are Hk rows apart
+  constexpr int LPR = CS::LPR;
+  const int row_mul = shared ? num_kv_heads : 1;
+  const int lane_vec = shared ? ((lane / LPR) * num_kv_heads + row % num_kv_heads) * LPR + lane % LPR : lane;
+  const int load_stride = kWave * row_mul;
+  const int32_t* bt = block_table + (int64_t)(shared ? s : row) * max_blocks;
   float* out = scores + (int64_t)row * max_blocks;
   // recent == 0: every entry of the row; else only the last `recent` full pages
   const int j_first = recent > 0 ? (nfull > recent ? nfull - recent : 0) : 0;
@@ -107,14 +114,16 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
   const int j0 = j_first + grp * kPagesPerGroup + wave;
 
   uint4 kb[2][NL], vb[2][NL];
-  if (j0 < nfull) CS::issue(kb[0], vb[0], k_pool, v_pool, PG::chunk_base(bt[j0], 0), lane);
+  if (j0 < nfull) CS::issue(kb[0], vb[0], k_pool, v_pool, PG::chunk_base(bt[j0], 0) * row_mul, lane_vec, load_stride);
   double sum = 0.0;
 #pragma unroll
   for (int u = 0; u < kUnits; ++u) {
     const int j = j0 + (u / NCH) * kWaves;
     if (u + 1 < kUnits) {
       const int jn = j0 + ((u + 1) / NCH) * kWaves;
-      if (jn < nfull) CS::issue(kb[(u + 1) & 1], vb[(u + 1) & 1], k_pool, v_pool, PG::chunk_base(bt[jn], (u + 1) % NCH), lane);
+      if (jn < nfull)
+        CS::issue(kb[(u + 1) & 1], vb[(u + 1) & 1], k_pool, v_pool, PG::chunk_base(bt[jn], (u + 1) % NCH) * row_mul,
+                  lane_vec, load_stride);
     }
     if (j >= j_end) break;
     if (j >= nfull) {
@@ -222,7 +231,7 @@ hipError_t launch(const ScoreArgs& a, hipStream_t stream) {
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL((score_blocks_kernel<T, D, B>), dim3((unsigned)grid), dim3(kThreads), 0, stream,
                      (const T*)a.k_pool, (const T*)a.v_pool, a.block_table, a.seq_lens, a.scores,
-                     a.num_kv_heads, a.max_blocks, groups_per_row, a.recent);
+                     a.num_kv_heads, a.max_blocks, groups_per_row, a.recent, a.shared ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -130,16 +130,17 @@ class PageLayout:
 
 
 def page_layout(wl: Workload, lens: List[int], base_seed: int, budget: Optional[int] = None,
-                steps: Optional[int] = None, extra_blocks: int = 0) -> PageLayout:
+                steps: Optional[int] = None, extra_blocks: int = 0, shared: bool = False) -> PageLayout:
     """Physical pages for `len(lens)` sequences x Hk rows (fold layers in by repeating `lens`).
 
     A row gets ceil(min(L, C)/B) pages for the pruned prompt and as many spare pages as it can still
     grow into before it reaches the budget (at least one).  Ids are consecutive in row order, or a
-    seeded random permutation of the whole pool when the workload asks for a shared, shuffled pool."""
+    seeded random permutation of the whole pool when the workload asks for a shared, shuffled pool.
+    shared=True lays out the head-shared cache: one row per sequence (the Hk axis has length 1)."""
     B = wl.block_size
     C = wl.budget if budget is None else budget
     steps = wl.steps if steps is None else steps
-    R, Hk = len(lens), wl.num_kv_heads
+    R, Hk = len(lens), (1 if shared else wl.num_kv_heads)
     init = [(min(L, C) + B - 1) // B for L in lens]
     grown = [(min(L + steps, C) + B - 1) // B for L in lens]
     max_blocks = max(max(grown), max(init)) + extra_blocks

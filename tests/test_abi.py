@@ -43,7 +43,7 @@ def _desc(**kw):
     (dict(head_dim=96), pe.PE_ERR_UNSUPPORTED), (dict(block_size=8), pe.PE_ERR_UNSUPPORTED),
     (dict(dtype=7), pe.PE_ERR_UNSUPPORTED), (dict(num_q_heads=30), pe.PE_ERR_INVALID_ARG),
     (dict(num_q_heads=128), pe.PE_ERR_UNSUPPORTED), (dict(num_seqs=0), pe.PE_ERR_INVALID_ARG),
-    (dict(max_blocks=0), pe.PE_ERR_INVALID_ARG)])
+    (dict(max_blocks=0), pe.PE_ERR_INVALID_ARG), (dict(layout=5), pe.PE_ERR_UNSUPPORTED)])
 def test_bad_descriptors(kw, want):
     d = _desc(**kw)
     L = pe.lib()
@@ -73,6 +73,18 @@ def test_null_pointers_and_bad_budget():
                               1 << 30, None) == pe.PE_ERR_INVALID_ARG   # max_seqlen > total_tokens
     misaligned = ctypes.c_void_p(0x1004)
     assert L.pe_score_blocks(ctypes.byref(d), misaligned, FAKE, FAKE, FAKE, FAKE, None, 0, None) == pe.PE_ERR_INVALID_ARG
+
+
+def test_shared_layout_host_checks():
+    d = _desc(layout=pe.PE_LAYOUT_SHARED)
+    L = pe.lib()
+    assert L.pe_score_evict(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, 256, None, FAKE, FAKE, None) == pe.PE_ERR_UNSUPPORTED
+    assert L.pe_append_paged_decode(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ctypes.c_void_p(0x2000),
+                                    FAKE, FAKE, FAKE, 4, ctypes.c_float(0.1), FAKE, FAKE, 1 << 30,
+                                    None) == pe.PE_ERR_UNSUPPORTED
+    # the shared prune keeps one more score row (the head mean) in its workspace
+    per_head = pe.pe_workspace_bytes(pe.PE_OP_PREFILL_PRUNE, _desc(), 4000)
+    assert pe.pe_workspace_bytes(pe.PE_OP_PREFILL_PRUNE, d, 4000) >= per_head + 4000 * 4
 
 
 def test_workspace_checks():
