@@ -45,6 +45,9 @@ def parse_args():
                          "procedure; the score sweep then drops out of the byte count too)")
     ap.add_argument("--fused-evict", action="store_true",
                     help="score + evict of a trigger step in one launch (pe_score_evict)")
+    ap.add_argument("--layout", choices=("per_head", "shared"), default="per_head",
+                    help="shared: one block-table row and one eviction decision per sequence, pages [B, Hk, D] "
+                         "(separate append and attention launches)")
     ap.add_argument("--graph", action="store_true", help="replay each step from captured HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-breakdown", action="store_true")
@@ -68,16 +71,16 @@ def traffic_from_profiles(workload):
     return None
 
 
-def build_engine(wl, seed, dev):
+def build_engine(wl, seed, dev, shared=False):
     import torch
     from paper_2509_04377_amd import binding as pe
     from paper_2509_04377_amd import synth
     from paper_2509_04377_amd.engine import LayeredCache
 
     lens = synth.context_lengths(wl, seed)
-    layout = synth.page_layout(wl, lens * wl.layers, seed)
+    layout = synth.page_layout(wl, lens * wl.layers, seed, shared=shared)
     eng = LayeredCache(wl.torch_dtype, wl.layers, wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim,
-                       wl.block_size, layout, wl.budget, dev)
+                       wl.block_size, layout, wl.budget, dev, shared=shared)
     total = sum(lens)
     ws = pe.alloc_workspace(pe.PE_OP_PREFILL_PRUNE, eng.per_layer[0].desc, total, device=dev)
     prune_ms = []
@@ -223,8 +226,9 @@ def main():
     if args.loads is not None:
         pe.pe_set_option(pe.PE_OPT_DECODE_LOADS, args.loads)
 
-    eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev)
-    eng.fused = not args.unfused
+    shared = args.layout == "shared"
+    eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev, shared)
+    eng.fused = not args.unfused and not shared
     eng.folded.cached_scores = args.cached_scores
     eng.folded.fused_evict = args.fused_evict
     L, S, Hk, Hq, D = wl.layers, wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim
@@ -309,7 +313,7 @@ def main():
         "config": {"workload": "%s: %d layers, %d seqs x %d KV heads (%d q heads), head_dim %d, page %d, context %s -> "
                                "budget %d" % (wl.name, L, S, Hk, Hq, D, wl.block_size, "/".join(map(str, wl.context)),
                                               wl.budget),
-                   "decode_splits": pe.pe_get_option(pe.PE_OPT_DECODE_SPLITS), "fused_append": eng.fused, "cached_scores": args.cached_scores, "fused_evict": args.fused_evict, "hip_graph": args.graph,
+                   "layout": args.layout, "decode_splits": pe.pe_get_option(pe.PE_OPT_DECODE_SPLITS), "fused_append": eng.fused, "cached_scores": args.cached_scores, "fused_evict": args.fused_evict, "hip_graph": args.graph,
                    "trigger_steps": n_trigger},
         "step_ms": {"p50": step_ms[len(step_ms) // 2], "p99": step_ms[min(len(step_ms) - 1, int(len(step_ms) * 0.99))],
                     "max": step_ms[-1]},

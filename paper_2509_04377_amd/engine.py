@@ -14,20 +14,20 @@ from . import binding as pe
 
 class LayeredCache:
     def __init__(self, dtype, layers, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, layout, budget,
-                 device="cuda"):
+                 device="cuda", shared=False):
         self.layers, self.S = layers, num_seqs
         self.Hk, self.Hq, self.D, self.B = num_kv_heads, num_q_heads, head_dim, block_size
         self.dtype, self.budget, self.device = dtype, int(budget), device
         R = layers * num_seqs
         assert layout.block_table.shape[0] == R
         self.folded = pe.PagedCache.create(dtype, R, num_kv_heads, num_q_heads, head_dim, block_size, layout, budget,
-                                           device)
+                                           device, shared=shared)
         f = self.folded
         self.per_layer: List[pe.PagedCache] = []
         for l in range(layers):
             sl = slice(l * num_seqs, (l + 1) * num_seqs)
             desc = pe.make_desc(dtype, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, layout.max_blocks,
-                                layout.num_phys_blocks)
+                                layout.num_phys_blocks, pe.PE_LAYOUT_SHARED if shared else pe.PE_LAYOUT_PER_HEAD)
             c = pe.PagedCache(desc, f.k_pool, f.v_pool, f.block_table[sl], f.seq_lens[sl], f.spare[sl],
                               f.spare_used[sl], f.freed_phys[sl], f.evicted_logical[sl], f.scores[sl], int(budget))
             self.per_layer.append(c)
@@ -38,7 +38,7 @@ class LayeredCache:
         for l, c in enumerate(self.per_layer):
             c.decode_ws = self.decode_ws
             c.seq_lens_alt = f.seq_lens_alt[l * num_seqs:(l + 1) * num_seqs]
-        self.fused = True
+        self.fused = not shared   # the one-launch append + attention exists for the per-head layout only
         self.host_lens = [0] * num_seqs   # the same in every layer
 
     def prefill_prune_layer(self, layer, k_in, v_in, cu_seqlens, max_seqlen, kept_idx_out=None, workspace=None):
