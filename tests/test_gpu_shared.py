@@ -275,3 +275,52 @@ def run_shared_loop(wl, steps, layer=0, cached_scores=False, policy=0, protect_f
 def test_shared_decode_loop(wl, steps, n_want, kw):
     print("case shared loop", wl.name, kw, flush=True)
     assert run_shared_loop(wl, steps, **kw) == n_want
+
+
+@pytest.mark.parametrize("wl", [synth.LLAMA31_8B, synth.LLAMA32_3B], ids=lambda w: w.name)
+def test_shared_full_size_one_layer(wl):
+    """A benchmark shape at its full batch and budget in the head-shared layout, through the layered driver
+    the benchmark uses (two layers in one pool, layer 1 compared): every per-head score, every decision, the
+    table and every attention output against the oracle, for a trigger step and a plain step."""
+    from paper_2509_04377_amd.engine import LayeredCache
+    print("case shared full size", wl.name, flush=True)
+    layers, l = 2, 1
+    S, Hk, Hq, D, B, C = wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim, wl.block_size, wl.budget
+    lens = [C] * S
+    layout = synth.page_layout(wl, lens * layers, SEED, steps=4, shared=True)
+    eng = LayeredCache(wl.torch_dtype, layers, S, Hk, Hq, D, B, layout, C, DEV, shared=True)
+    cu = torch.tensor(np.arange(S + 1) * C, dtype=torch.int32)
+    prompts = []
+    for i in range(layers):
+        k_in, v_in, _ = synth.prompt_kv(wl, i, lens, SEED)
+        eng.prefill_prune_layer(i, k_in.to(DEV), v_in.to(DEV), cu.to(DEV), C)
+        prompts.append((k_in, v_in))
+    eng.set_host_lens(lens)
+    torch.cuda.synchronize()
+    P = layout.num_phys_blocks
+    kp = np.zeros((P, B, Hk, D), np.float32); vp = np.zeros_like(kp)
+    table = i32(layout.block_table[l * S:(l + 1) * S, 0]).copy()
+    o_lens, _ = osh.prefill_prune(f32(prompts[l][0]), f32(prompts[l][1]), i32(cu), C, kp, vp, table)
+    oc = osh.SharedOracleCache(kp, vp, table, o_lens, i32(layout.spare[l * S:(l + 1) * S, 0]).copy(),
+                               np.zeros(S, np.int32), np.full(S, -1, np.int32), C)
+    g = torch.Generator().manual_seed(SEED)
+    out = torch.empty((layers, S, Hq, D), dtype=wl.torch_dtype, device=DEV)
+    for step in range(2):
+        nk = torch.randn((layers, S, Hk, D), generator=g).to(wl.torch_dtype)
+        nv = torch.randn((layers, S, Hk, D), generator=g).to(wl.torch_dtype)
+        q = torch.randn((layers, S, Hq, D), generator=g).to(wl.torch_dtype)
+        want, oscores, oev, _ = osh.decode_step(oc, f32(nk[l]), f32(nv[l]), f32(q[l]))
+        trig = eng.decode_step(nk.to(DEV), nv.to(DEV), q.to(DEV), out)
+        torch.cuda.synchronize()
+        gl = eng.per_layer[l]
+        assert trig == (step == 0)
+        assert np.array_equal(gl.block_table.cpu().numpy(), oc.block_table)
+        assert np.array_equal(gl.seq_lens.cpu().numpy(), oc.seq_lens)
+        if trig:
+            assert np.array_equal(gl.evicted_logical.cpu().numpy(), oev)
+            gs = gl.scores.cpu().numpy()
+            fin = np.isfinite(oscores)
+            assert np.array_equal(np.isinf(gs), np.isinf(oscores)) and _ulp(gs[fin], oscores[fin]).max() <= 1
+        e2, emax = rel_err(f32(out[l]), want)
+        print("shared full size step %d attention error %.3g %.3g" % (step, e2, emax), flush=True)
+        assert e2 <= TOL[wl.dtype] and emax <= TOL[wl.dtype]
