@@ -27,6 +27,8 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kChunk = 1024;  // tokens per chunk in kernels 3 and 4 (4 per thread)
 constexpr int kTokPerThread = kChunk / kThreads;
+constexpr int kSweepLoads = 4;  // token sweep: wave-loads of K (and of V) per step
+constexpr int kSweepIters = 4;  // and steps per wave (8 measured the same)
 
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -68,27 +70,30 @@ __global__ __launch_bounds__(kThreads) void token_scores_kernel(const T* __restr
   using G = RowGeom<T, D>;
   constexpr int LPR = G::kLanesPerRow;
   constexpr int TPL = G::kTokensPerLoad;
-  constexpr int NL = 4;
+  constexpr int NL = kSweepLoads;
   constexpr int kRowsPerStep = NL * TPL;
-  constexpr int kIters = 4;
+  constexpr int kIters = kSweepIters;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   const int grp = lane / LPR;
-  const int64_t row0 = ((int64_t)blockIdx.x * kWaves + wave) * (kIters * kRowsPerStep);
+  constexpr int kRowsPerWave = kIters * kRowsPerStep;
+  constexpr int kRowsPerGroup = kWaves * kRowsPerWave;
+  __shared__ float sm_score[kRowsPerGroup];  // the workgroup's scores in row order, stored head by head at the end
+  const int64_t group_row0 = (int64_t)blockIdx.x * kRowsPerGroup;
+  const int64_t row0 = group_row0 + (int64_t)wave * kRowsPerWave;
 
   uint4 kb[2][NL], vb[2][NL];
+  // loads are unconditional: a row past the end is read from the last row instead (its result is never
+  // stored), so the compiler keeps the order of outstanding loads and the next group stays in flight
+  const int64_t last_row = total_rows - 1;
+  const int u = lane % LPR;
   auto issue = [&](int buf, int64_t base_row) {
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
       const int64_t r = base_row + i * TPL + grp;
-      if (r < total_rows) {
-        const int64_t vec = (base_row + i * TPL) * LPR + lane;
-        kb[buf][i] = load_vec_stream(k_in, vec);
-        vb[buf][i] = load_vec_stream(v_in, vec);
-      } else {
-        kb[buf][i] = make_uint4(0u, 0u, 0u, 0u);
-        vb[buf][i] = make_uint4(0u, 0u, 0u, 0u);
-      }
+      const int64_t vec = (r < last_row ? r : last_row) * LPR + u;
+      kb[buf][i] = load_vec_stream(k_in, vec);
+      vb[buf][i] = load_vec_stream(v_in, vec);
     }
   };
   issue(0, row0);
@@ -106,16 +111,25 @@ __global__ __launch_bounds__(kThreads) void token_scores_kernel(const T* __restr
     }
     const double ratio = token_ratio_from_partials<NL, LPR>(part, lane);
     // the lane at position 2*k of its row group (k < NL) stores the row of wave-load bit_reverse(k)
-    const int uu = lane % LPR;
+    const int uu = u;
     if ((uu & 1) == 0 && uu < 2 * NL) {
       const int i = bit_reverse<ilog2(NL)>(uu >> 1);
       const int64_t r = base_row + i * TPL + grp;
-      if (r < total_rows) {
-        const int64_t tok = r / num_kv_heads;
-        const int h = (int)(r % num_kv_heads);
-        scores[(int64_t)h * total_tokens + tok] = (float)ratio;
-      }
+      if (r < total_rows) sm_score[(int)(r - group_row0)] = (float)ratio;
     }
+  }
+  // The group's rows are (token, head) pairs in token-major order; the score array is head-major.  Written
+  // head by head, the tokens of one head are consecutive floats (a full 128-byte line for 32 tokens).
+  __syncthreads();
+  const int64_t group_end = group_row0 + kRowsPerGroup < total_rows ? group_row0 + kRowsPerGroup : total_rows;
+  if (group_row0 >= group_end) return;
+  const int64_t tok_lo = group_row0 / num_kv_heads;
+  const int ntok = (int)((group_end - 1) / num_kv_heads - tok_lo) + 1;
+  for (int p = (int)threadIdx.x; p < ntok * num_kv_heads; p += kThreads) {
+    const int h = p / ntok;
+    const int64_t tok = tok_lo + (p - h * ntok);
+    const int64_t r = tok * num_kv_heads + h;
+    if (r >= group_row0 && r < group_end) scores[(int64_t)h * total_tokens + tok] = sm_score[(int)(r - group_row0)];
   }
 }
 
@@ -403,7 +417,7 @@ hipError_t launch(const PruneArgs& a, hipStream_t stream) {
   const int64_t total_rows = a.total_tokens * a.num_kv_heads;
   hipError_t e;
   if (total_rows > 0) {
-    const int64_t rows_per_group = (int64_t)kWaves * 4 * 4 * G::kTokensPerLoad;
+    const int64_t rows_per_group = (int64_t)kWaves * kSweepIters * kSweepLoads * G::kTokensPerLoad;
     const int64_t grid = (total_rows + rows_per_group - 1) / rows_per_group;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((token_scores_kernel<T, D>), dim3((unsigned)grid), dim3(kThreads), 0, stream,
