@@ -362,14 +362,38 @@ class PagedCache:
         B = self.desc.block_size
         return any(n > 0 and n % B == 0 and n >= self.budget for n in self.host_lens)
 
+    def _sp(self, name, dtype=None):
+        """Checked device pointer of one of the cache's own tensors, remembered per tensor object (the state
+        tensors are passed on every call of a decode loop; their checks need not be repeated)."""
+        t = getattr(self, name)
+        memo = self.__dict__.setdefault("_ptr_memo", {})
+        hit = memo.get(name)
+        if hit is not None and hit[0] is t:
+            return hit[1]
+        alt = memo.get(name + "~")          # the two lengths arrays alternate
+        if alt is not None and alt[0] is t:
+            memo[name], memo[name + "~"] = alt, hit
+            return alt[1]
+        p = _ptr(t, name, dtype)
+        if hit is not None:
+            memo[name + "~"] = hit
+        memo[name] = (t, p)
+        return p
+
     def append_paged_decode(self, new_k, new_v, q, out, softmax_scale=None):
         if softmax_scale is None:
             softmax_scale = float(self.desc.head_dim) ** -0.5
         if self.seq_lens_alt is None:
             self.seq_lens_alt = torch.empty_like(self.seq_lens)
-        pe_append_paged_decode(self.desc, new_k, new_v, q, self.k_pool, self.v_pool, self.block_table, self.seq_lens,
-                               self.seq_lens_alt, self.freed_phys, self.spare, self.spare_used, softmax_scale, out,
-                               self.decode_ws)
+        if not _HostOnly.active:
+            i32 = torch.int32
+            wp, wn = _ws(self.decode_ws)
+            _check(lib().pe_append_paged_decode(
+                ctypes.byref(self.desc), _ptr(new_k, "new_k"), _ptr(new_v, "new_v"), _ptr(q, "q"),
+                self._sp("k_pool"), self._sp("v_pool"), self._sp("block_table", i32), self._sp("seq_lens", i32),
+                self._sp("seq_lens_alt", i32), self._sp("freed_phys", i32), self._sp("spare", i32),
+                self._sp("spare_used", i32), int(self.spare.shape[-1]), ctypes.c_float(softmax_scale),
+                _ptr(out, "out"), wp, wn, _stream()), "pe_append_paged_decode")
         self.seq_lens, self.seq_lens_alt = self.seq_lens_alt, self.seq_lens
 
     def decode_step(self, new_k, new_v, q, out, softmax_scale=None, fused=True):
@@ -428,11 +452,21 @@ class PagedCache:
                             for f, n in zip(full, self.host_lens)]
 
     def append_kv(self, new_k, new_v):
-        pe_append_kv(self.desc, new_k, new_v, self.k_pool, self.v_pool, self.block_table, self.seq_lens,
-                     self.freed_phys, self.spare, self.spare_used)
+        if _HostOnly.active:
+            return
+        i32 = torch.int32
+        _check(lib().pe_append_kv(ctypes.byref(self.desc), _ptr(new_k, "new_k"), _ptr(new_v, "new_v"),
+                                  self._sp("k_pool"), self._sp("v_pool"), self._sp("block_table", i32),
+                                  self._sp("seq_lens", i32), self._sp("freed_phys", i32), self._sp("spare", i32),
+                                  self._sp("spare_used", i32), int(self.spare.shape[-1]), _stream()), "pe_append_kv")
 
     def paged_decode(self, q, out, softmax_scale=None):
         if softmax_scale is None:
             softmax_scale = float(self.desc.head_dim) ** -0.5
-        pe_paged_decode(self.desc, q, self.k_pool, self.v_pool, self.block_table, self.seq_lens, softmax_scale, out,
-                        self.decode_ws)
+        if _HostOnly.active:
+            return
+        wp, wn = _ws(self.decode_ws)
+        _check(lib().pe_paged_decode(ctypes.byref(self.desc), _ptr(q, "q"), self._sp("k_pool"), self._sp("v_pool"),
+                                     self._sp("block_table", torch.int32), self._sp("seq_lens", torch.int32),
+                                     ctypes.c_float(softmax_scale), _ptr(out, "out"), wp, wn, _stream()),
+               "pe_paged_decode")
