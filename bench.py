@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--layout", choices=("per_head", "shared"), default="per_head",
                     help="shared: one block-table row and one eviction decision per sequence, pages [B, Hk, D] "
                          "(separate append and attention launches)")
+    ap.add_argument("--stagger", action="store_true",
+                    help="prompts of budget - (s mod B) tokens instead of the workload's: sequences reach their page "
+                         "boundaries at different steps, as in a serving batch (the prefill prune is then a plain copy)")
     ap.add_argument("--graph", action="store_true", help="replay each step from captured HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-breakdown", action="store_true")
@@ -73,13 +76,15 @@ def traffic_from_profiles(workload):
     return None
 
 
-def build_engine(wl, seed, dev, shared=False):
+def build_engine(wl, seed, dev, shared=False, stagger=False):
     import torch
     from paper_2509_04377_amd import binding as pe
     from paper_2509_04377_amd import synth
     from paper_2509_04377_amd.engine import LayeredCache
 
     lens = synth.context_lengths(wl, seed)
+    if stagger:   # just under the budget, a different distance for every sequence: page boundaries never line up
+        lens = [wl.budget - (s % wl.block_size) for s in range(wl.num_seqs)]
     layout = synth.page_layout(wl, lens * wl.layers, seed, shared=shared)
     eng = LayeredCache(wl.torch_dtype, wl.layers, wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim,
                        wl.block_size, layout, wl.budget, dev, shared=shared)
@@ -229,7 +234,7 @@ def main():
         pe.pe_set_option(pe.PE_OPT_DECODE_LOADS, args.loads)
 
     shared = args.layout == "shared"
-    eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev, shared)
+    eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev, shared, args.stagger)
     eng.fused = not args.unfused and not shared
     eng.folded.cached_scores = args.cached_scores
     eng.folded.fused_evict = args.fused_evict
@@ -284,13 +289,15 @@ def main():
             samples.append((state["e0"], e, 1, per_launch))
 
     step_events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    n_trigger = 0
+    n_trigger = 0        # steps on which some sequence evicts
+    n_trigger_seqs = 0   # sequence-evictions over the timed region (each scores its own pages)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     step_events[0].record()
     for st in range(args.steps):
         i = (args.warmup + st) % ring
         sampled = args.sample_every > 0 and st % args.sample_every == args.sample_every // 2
+        n_trigger_seqs += sum(eng._triggers())
         if stepper is not None:
             trig = stepper.step()
             if sampled and not trig and eng.fused:   # a plain step is L attention launches and nothing else
@@ -315,13 +322,14 @@ def main():
         "config": {"workload": "%s: %d layers, %d seqs x %d KV heads (%d q heads), head_dim %d, page %d, context %s -> "
                                "budget %d" % (wl.name, L, S, Hk, Hq, D, wl.block_size, "/".join(map(str, wl.context)),
                                               wl.budget),
-                   "layout": args.layout, "decode_splits": pe.pe_get_option(pe.PE_OPT_DECODE_SPLITS), "fused_append": eng.fused, "cached_scores": args.cached_scores, "fused_evict": args.fused_evict, "hip_graph": args.graph,
-                   "trigger_steps": n_trigger},
+                   "layout": args.layout, "stagger": args.stagger, "decode_splits": pe.pe_get_option(pe.PE_OPT_DECODE_SPLITS), "fused_append": eng.fused, "cached_scores": args.cached_scores, "fused_evict": args.fused_evict, "hip_graph": args.graph,
+                   "trigger_steps": n_trigger, "sequence_evictions": n_trigger_seqs},
         "step_ms": {"p50": step_ms[len(step_ms) // 2], "p99": step_ms[min(len(step_ms) - 1, int(len(step_ms) * 0.99))],
                     "max": step_ms[-1]},
         "prefill_prune": {"ms_per_layer": sorted(prune_ms)[len(prune_ms) // 2],
                           "sweep_GBps": prune_bytes / (sorted(prune_ms)[len(prune_ms) // 2] * 1e-3) / 1e9},
     }
+    result["roofline"] = None   # stays None when no step could be sampled (graph replay of trigger-only runs)
     if samples:
         n_launch = sum(n for _, _, n, _ in samples)
         avg_dur = sum(a.elapsed_time(b) * 1e-3 for a, b, _, _ in samples) / n_launch
@@ -336,8 +344,8 @@ def main():
     if samples:
         mean_cached = avg_bytes                                              # per layer launch
         pages_scored = 1 if args.cached_scores else wl.budget // wl.block_size     # per row per trigger
-        score_bytes = L * S * Hk * pages_scored * wl.block_size * D * 2 * elem
-        total_bytes = mean_cached * L * args.steps + score_bytes * n_trigger
+        score_bytes = L * Hk * pages_scored * wl.block_size * D * 2 * elem          # per evicting sequence
+        total_bytes = mean_cached * L * args.steps + score_bytes * n_trigger_seqs
         result["path_GBps"] = total_bytes / elapsed / 1e9
         result["path_frac_of_hbm_peak"] = result["path_GBps"] / HBM_PEAK_GBS
 

@@ -180,6 +180,17 @@ int pe_evict_blocks_cached(const pe_cache_desc* desc, float* scores_inout, int32
                            void* stream);
 
 /*
+ * (1) restricted to the sequences that (3) will act on: Alg. 3 scores pages only inside its "L % B == 0"
+ * branch, i.e. for a sequence whose newest page has just filled (and, reading G3, which is at budget).
+ * Rows of sequences that do not trigger at `budget_tokens` are neither read nor written (their entries of
+ * scores_inout keep whatever they held); rows of triggering sequences are written exactly as by (1).  With
+ * sequences that reach a page boundary at different steps this reads a fraction of what (1) reads.
+ */
+int pe_score_triggered_blocks(const pe_cache_desc* desc, const void* k_pool, const void* v_pool,
+                              const int32_t* block_table, const int32_t* seq_lens, int32_t budget_tokens,
+                              float* scores_inout, void* stream);
+
+/*
  * (1)+(3) in one launch -- the whole "if L % B == 0" branch of Alg. 3.  Equal in effect to pe_score_blocks
  * followed by pe_evict_blocks, except that only triggering sequences are scored: their rows' pages are swept
  * once, the running minimum is kept (ties: lowest index), the table row is compacted and seq_lens[s] -= B.

@@ -24,7 +24,8 @@ PE_OPT_DECODE_LOADS = 4
 
 EXPORTS = ["pe_workspace_bytes", "pe_status_string", "pe_version", "pe_set_option", "pe_get_option",
            "pe_score_blocks", "pe_prefill_prune", "pe_evict_blocks", "pe_paged_decode", "pe_append_kv",
-           "pe_append_paged_decode", "pe_score_recent_blocks", "pe_evict_blocks_cached", "pe_evict_blocks_ex", "pe_score_evict"]
+           "pe_append_paged_decode", "pe_score_recent_blocks", "pe_evict_blocks_cached", "pe_evict_blocks_ex", "pe_score_evict",
+           "pe_score_triggered_blocks"]
 
 
 class pe_cache_desc(ctypes.Structure):
@@ -77,6 +78,8 @@ def lib():
         L.pe_prefill_prune.argtypes = [dp, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.pe_evict_blocks.restype = ctypes.c_int
         L.pe_evict_blocks.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp]
+        L.pe_score_triggered_blocks.restype = ctypes.c_int
+        L.pe_score_triggered_blocks.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp]
         L.pe_score_evict.restype = ctypes.c_int
         L.pe_score_evict.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.pe_paged_decode.restype = ctypes.c_int
@@ -206,6 +209,16 @@ def pe_evict_blocks(desc, scores, block_table, seq_lens, budget_tokens, evicted_
                                  _ptr(block_table, "block_table", torch.int32), _ptr(seq_lens, "seq_lens", torch.int32),
                                  int(budget_tokens), _ptr(evicted_logical_out, "evicted_logical_out", torch.int32),
                                  _ptr(freed_phys_out, "freed_phys_out", torch.int32), _stream()), "pe_evict_blocks")
+
+
+def pe_score_triggered_blocks(desc, k_pool, v_pool, block_table, seq_lens, budget_tokens, scores_inout):
+    if _HostOnly.active:
+        return
+    _check(lib().pe_score_triggered_blocks(ctypes.byref(desc), _ptr(k_pool, "k_pool"), _ptr(v_pool, "v_pool"),
+                                           _ptr(block_table, "block_table", torch.int32),
+                                           _ptr(seq_lens, "seq_lens", torch.int32), int(budget_tokens),
+                                           _ptr(scores_inout, "scores_inout", torch.float32), _stream()),
+           "pe_score_triggered_blocks")
 
 
 def pe_score_evict(desc, k_pool, v_pool, block_table, seq_lens, budget_tokens, scores_out, evicted_logical_out,
@@ -414,6 +427,10 @@ class PagedCache:
     def score_blocks(self):
         pe_score_blocks(self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, self.scores)
 
+    def score_triggered_blocks(self):
+        pe_score_triggered_blocks(self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, self.budget,
+                                  self.scores)
+
     def evict_blocks(self):
         pe_evict_blocks(self.desc, self.scores, self.block_table, self.seq_lens, self.budget, self.evicted_logical,
                         self.freed_phys)
@@ -426,7 +443,7 @@ class PagedCache:
             o = self.evict_opts
             opts = pe_evict_opts(o.policy, o.protect_first, o.protect_last, o.share_heads, 0)
             if o.policy != PE_POLICY_OLDEST:
-                self.score_blocks()
+                self.score_triggered_blocks()
             pe_evict_blocks_ex(self.desc, opts, self.scores if o.policy != PE_POLICY_OLDEST else None,
                                self.block_table, self.seq_lens, self.budget, self.evicted_logical, self.freed_phys)
             return
@@ -434,8 +451,8 @@ class PagedCache:
             pe_score_evict(self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, self.budget, None,
                            self.evicted_logical, self.freed_phys)
             return
-        if not self.cached_scores:
-            self.score_blocks()
+        if not self.cached_scores:   # Alg. 3: score the pages of the sequences that evict now, then evict
+            self.score_triggered_blocks()
             self.evict_blocks()
             return
         full = [n // B for n in self.host_lens]

@@ -102,7 +102,7 @@ size_t pe_workspace_bytes(int op, const pe_cache_desc* desc, int64_t total_token
 
 namespace {
 int score_blocks_impl(const pe_cache_desc* desc, const void* k_pool, const void* v_pool, const int32_t* block_table,
-                      const int32_t* seq_lens, float* scores_out, int recent, void* stream);
+                      const int32_t* seq_lens, float* scores_out, int recent, void* stream, int budget = 0);
 }
 
 int pe_score_blocks(const pe_cache_desc* desc, const void* k_pool, const void* v_pool, const int32_t* block_table,
@@ -120,9 +120,17 @@ int pe_score_recent_blocks(const pe_cache_desc* desc, const void* k_pool, const 
   return score_blocks_impl(desc, k_pool, v_pool, block_table, seq_lens, scores_inout, recent, stream);
 }
 
+int pe_score_triggered_blocks(const pe_cache_desc* desc, const void* k_pool, const void* v_pool,
+                              const int32_t* block_table, const int32_t* seq_lens, int32_t budget_tokens,
+                              float* scores_inout, void* stream) {
+  if (desc == nullptr) return PE_ERR_INVALID_ARG;
+  if (budget_tokens <= 0 || desc->block_size <= 0 || budget_tokens % desc->block_size != 0) return PE_ERR_INVALID_ARG;
+  return score_blocks_impl(desc, k_pool, v_pool, block_table, seq_lens, scores_inout, 0, stream, budget_tokens);
+}
+
 namespace {
 int score_blocks_impl(const pe_cache_desc* desc, const void* k_pool, const void* v_pool, const int32_t* block_table,
-                      const int32_t* seq_lens, float* scores_out, int recent, void* stream) {
+                      const int32_t* seq_lens, float* scores_out, int recent, void* stream, int budget) {
   const int st = check_desc(desc);
   if (st != PE_OK) return st;
   if (!k_pool || !v_pool || !block_table || !seq_lens || !scores_out) return PE_ERR_INVALID_ARG;
@@ -141,6 +149,7 @@ int score_blocks_impl(const pe_cache_desc* desc, const void* k_pool, const void*
   a.is_bf16 = desc->dtype == PE_BF16;
   a.shared = desc->layout == PE_LAYOUT_SHARED;
   a.recent = recent;
+  a.budget = budget;
   return pe::launch_score_blocks(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
 }  // namespace

@@ -18,6 +18,7 @@ struct ScoreArgs {
   bool is_bf16;
   int recent = 0;  // 0: score every page; n > 0: only the n most recently filled pages of each row
   bool shared = false;  // one table row per sequence, pages [B][Hk][D]
+  int budget = 0;       // > 0: score only the sequences that trigger an eviction at this budget
 };
 hipError_t launch_score_blocks(const ScoreArgs& a, hipStream_t stream);
 

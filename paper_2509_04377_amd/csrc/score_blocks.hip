@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
                                                                 const int32_t* __restrict__ seq_lens,
                                                                 float* __restrict__ scores, int num_kv_heads,
                                                                 int max_blocks, int groups_per_row, int recent,
-                                                                int shared) {
+                                                                int shared, int budget) {
   using PG = PageGeom<T, D, B>;
   using CS = typename PG::CS;
   constexpr int NL = CS::NL;
@@ -99,7 +99,10 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
   const int row = (int)(blockIdx.x / groups_per_row);
   const int grp = (int)(blockIdx.x % groups_per_row);
   const int s = row / num_kv_heads;
-  const int nfull_raw = seq_lens[s] / B;
+  const int len = seq_lens[s];
+  // budget > 0: only sequences that are about to evict (newest page just filled, at budget) are scored
+  if (budget > 0 && !(len > 0 && len % B == 0 && len >= budget)) return;
+  const int nfull_raw = len / B;
   const int nfull = nfull_raw < max_blocks ? nfull_raw : max_blocks;  // never index past the table row
   // shared: one table row per sequence and pages of [B][Hk][D]: the token rows of this head are Hk rows apart
   constexpr int LPR = CS::LPR;
@@ -231,7 +234,7 @@ hipError_t launch(const ScoreArgs& a, hipStream_t stream) {
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL((score_blocks_kernel<T, D, B>), dim3((unsigned)grid), dim3(kThreads), 0, stream,
                      (const T*)a.k_pool, (const T*)a.v_pool, a.block_table, a.seq_lens, a.scores,
-                     a.num_kv_heads, a.max_blocks, groups_per_row, a.recent, a.shared ? 1 : 0);
+                     a.num_kv_heads, a.max_blocks, groups_per_row, a.recent, a.shared ? 1 : 0, a.budget);
   return hipGetLastError();
 }
 

@@ -81,6 +81,9 @@ def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=Fals
                             want_sc[s_, h_, j:-1] = oscores[s_, h_, j + 1:]
                             want_sc[s_, h_, -1] = np.inf
                 oscores = want_sc
+            if not cached_scores:   # only the sequences that evict at this step are scored (Alg. 3)
+                rows = (oev >= 0).any(axis=1)
+                gs, oscores = gs[rows], oscores[rows]
             assert np.array_equal(np.isinf(gs), np.isinf(oscores)), where
             fin = np.isfinite(oscores)
             assert _ulp(gs[fin], oscores[fin]).max() <= 1, where
@@ -121,6 +124,19 @@ def test_cached_scores_give_the_same_decisions(wl, steps, n_want):
     print("case loop cached scores", wl.name, flush=True)
     n_ev, _ = run_loop(wl, steps, cached_scores=True)
     assert n_ev == n_want
+
+
+@pytest.mark.parametrize("kw", [{}, dict(fused_evict=True), dict(cached_scores=True), dict(fused=False),
+                                dict(evict_opts=dict(policy=0, protect_first=1, share_heads=True))])
+def test_staggered_triggers(kw):
+    """Prompts a little under the budget and of different lengths: the sequences reach the budget, and later
+    their page boundaries, at different steps, so most trigger steps evict from only some of them."""
+    print("case loop staggered", kw, flush=True)
+    wl = synth.LLAMA32_1B.with_(num_seqs=6, context=(470, 512), budget=512)
+    lens = synth.context_lengths(wl, SEED)
+    assert len(set(L % wl.block_size for L in lens)) >= 4
+    n_ev, _ = run_loop(wl, 60, **kw)
+    assert n_ev >= 8          # many more trigger steps than the 4 a lockstep batch would see in 60 steps
 
 
 @pytest.mark.parametrize("B,fused_evict", [(64, False), (128, False), (64, True)])

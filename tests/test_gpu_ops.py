@@ -73,6 +73,27 @@ def test_score_blocks_random(dt, D, B):
     assert (ulp != 0).mean() < 1e-3, "scores should be bit-equal except at rare rounding boundaries"
 
 
+def test_score_triggered_blocks_touches_only_sequences_that_evict():
+    print("case score_triggered_blocks", flush=True)
+    B, D, Hk = 16, 128, 3
+    C = 4 * B
+    lens = [8 * B, 8 * B - 1, 3 * B, 0, 4 * B, 9 * B + 5, 20 * B]   # triggers: 0, 4, 6 (3*B is under budget)
+    k_pool, v_pool, table, sl = make_paged(150, lens, Hk, D, B, torch.bfloat16, extra=2)
+    S, _, mb = table.shape
+    desc = pe.make_desc(torch.bfloat16, S, Hk, Hk, D, B, mb, k_pool.shape[0])
+    got = torch.full((S, Hk, mb), -123.0, dtype=torch.float32, device=DEV)
+    pe.pe_score_triggered_blocks(desc, k_pool.to(DEV), v_pool.to(DEV), table.to(DEV), sl.to(DEV), C, got)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    want = oracle.score_blocks(f32(k_pool), f32(v_pool), i32(table), i32(sl))
+    for s, L in enumerate(lens):
+        if L > 0 and L % B == 0 and L >= C:
+            assert np.array_equal(got[s].view(np.int32), want[s].view(np.int32)), s   # bf16: sums are exact
+        else:
+            assert np.all(got[s] == np.float32(-123.0)), s
+    assert [s for s in range(S) if got[s, 0, 0] != np.float32(-123.0)] == [0, 4, 6]
+
+
 def test_score_blocks_closed_forms():
     print("case score_blocks_closed_forms", flush=True)
     B, D, Hk = 16, 128, 2
