@@ -196,7 +196,8 @@ int pe_score_triggered_blocks(const pe_cache_desc* desc, const void* k_pool, con
  * once, the running minimum is kept (ties: lowest index), the table row is compacted and seq_lens[s] -= B.
  * scores_out: NULL, or [S][Hk][max_blocks] fp32; rows of triggering sequences receive the scores the decision
  * was taken on (before compaction; entries j >= seq_lens[s]/B are +INF), rows of other sequences are left
- * untouched.  evicted_logical_out / freed_phys_out as in (3).
+ * untouched.  evicted_logical_out / freed_phys_out as in (3).  One workgroup per sequence: efficient when most
+ * sequences of the batch trigger together, short of parallelism when only a few do (use the two calls then).
  */
 int pe_score_evict(const pe_cache_desc* desc, const void* k_pool, const void* v_pool, int32_t* block_table,
                    int32_t* seq_lens, int32_t budget_tokens, float* scores_out, int32_t* evicted_logical_out,
