@@ -25,7 +25,9 @@ _i32p = ctypes.POINTER(ctypes.c_int32)
 def _load():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # PE_ORACLE_LIB: a test (tests/test_oracle_mutants.py) points this at a deliberately broken build of
+        # the oracle to check that the pins notice; nothing else sets it
+        path = os.environ.get("PE_ORACLE_LIB") or _build.build(force=False)
         lib = ctypes.CDLL(path)
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_token_ratio.restype = ctypes.c_double

@@ -109,3 +109,34 @@ def test_under_budget_prompt_grows_then_evicts():
     assert lens_at_attention == want
     first_evict = [i for i, h in enumerate(history) if np.all(h[2] >= 0)]
     assert first_evict[0] == 24 and first_evict == [24, 40, 56]
+
+
+def test_append_consumes_the_freed_page_once():
+    """A row at a page boundary takes the page it has just freed and forgets it: B tokens later, with no
+    eviction in between, the next page comes from the spare list.  Rows elsewhere in a page touch no
+    bookkeeping, and every new K/V row lands in (tail page, slot len % B)."""
+    rng = np.random.default_rng(70)
+    S, Hk, D, B, mb, n_spare = 2, 2, 64, 16, 5, 2
+    k = np.zeros((40, B, D), np.float32); v = np.zeros_like(k)
+    table = np.full((S, Hk, mb), -1, np.int32)
+    table[0, :, 0] = [3, 4]                          # sequence 0: one full page per row -> boundary
+    table[1, :, 0] = [5, 6]                          # sequence 1: 5 tokens -> mid-page
+    lens = np.array([B, 5], np.int32)
+    freed = np.array([[11, -1], [-1, -1]], np.int32)   # only row (0, 0) holds a freed page
+    spare = (20 + np.arange(S * Hk * n_spare, dtype=np.int32)).reshape(S, Hk, n_spare)
+    used = np.zeros((S, Hk), np.int32)
+    for step in range(B + 1):
+        nk = rng.standard_normal((S, Hk, D)).astype(np.float32); nv = rng.standard_normal((S, Hk, D)).astype(np.float32)
+        before = lens.copy()
+        oracle.append_kv(nk, nv, k, v, table, lens, freed, spare, used)
+        for s in range(S):
+            for h in range(Hk):
+                page = table[s, h, before[s] // B]
+                assert np.array_equal(k[page, before[s] % B], nk[s, h]) and np.array_equal(v[page, before[s] % B], nv[s, h])
+        if step == 0:
+            assert table[0, 0, 1] == 11 and table[0, 1, 1] == spare[0, 1, 0]
+            assert freed[0, 0] == -1 and used.tolist() == [[0, 1], [0, 0]]
+    # step B was sequence 0's next boundary: both rows took a spare page, the freed one was not reused
+    assert table[0, 0, 2] == spare[0, 0, 0] and table[0, 1, 2] == spare[0, 1, 1]
+    assert used[0].tolist() == [1, 2] and np.all(freed == -1)
+    assert lens.tolist() == [2 * B + 1, 5 + B + 1] and table[1, 0, 1] == spare[1, 0, 0]
