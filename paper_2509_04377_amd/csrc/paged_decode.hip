@@ -22,6 +22,10 @@
 // the last split's workgroup links a new page if the tail page is full and stores the rows into the
 // pool, and the new lengths go to a second array (the caller swaps the two), so no workgroup can see a
 // length that another one has already bumped.
+//
+// The SHARED variant reads the head-shared cache layout: one table row per sequence and pages of
+// [B][Hk][D], so the token rows of this workgroup's head are Hk rows apart (a wave-load is then TPL runs
+// of one row each instead of one contiguous KiB).  Everything after the loads is the same.
 #include "pe_device.h"
 #include "pe_launch.h"
 
