@@ -55,7 +55,7 @@ int check_workspace(const void* ws, size_t have, size_t need) {
 
 extern "C" {
 
-int pe_version(void) { return 100; }
+int pe_version(void) { return 200; }  // 0.2.0: pe_cache_desc gained `layout`
 
 const char* pe_status_string(int status) {
   switch (status) {
