@@ -109,6 +109,14 @@ def test_tiny_full(fused):
     print("tiny worst attention error", worst, flush=True)
 
 
+def test_many_kv_heads_without_grouping():
+    """32 KV heads, one query head each (more heads than a workgroup has waves, in every kernel that loops
+    over the heads of a sequence)."""
+    print("case loop many heads", flush=True)
+    n_ev, _ = run_loop(synth.TINY.with_(num_kv_heads=32, num_q_heads=32, num_seqs=2), 20)
+    assert n_ev == 2
+
+
 def test_tiny_under_budget_growth():
     print("case loop tiny under budget", flush=True)
     wl = synth.TINY.with_(context=(40,), budget=64)
