@@ -235,6 +235,8 @@ def main():
 
     shared = args.layout == "shared"
     eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev, shared, args.stagger)
+    # shared layout: the combined call is two launches inside the library; issue them separately here so that the
+    # events bracket the attention kernel alone
     eng.fused = not args.unfused and not shared
     eng.folded.cached_scores = args.cached_scores
     eng.folded.fused_evict = args.fused_evict

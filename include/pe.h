@@ -66,8 +66,7 @@ typedef enum {
  *   [B][Hk][D] (token slot, head, element), ONE decision per sequence: a token's / page's score is the mean
  *   over the KV heads of the per-head fp32 scores (summed in head order in fp64, rounded once), and the token
  *   / page is dropped for all heads.  Array shapes then lose their Hk dimension where the documentation
- *   below says so ("shared: ...").  pe_append_paged_decode and pe_score_evict are per-head only
- *   (PE_ERR_UNSUPPORTED otherwise). */
+ *   below says so ("shared: ...").  pe_score_evict is per-head only (PE_ERR_UNSUPPORTED otherwise). */
 typedef enum { PE_LAYOUT_PER_HEAD = 0, PE_LAYOUT_SHARED = 1 } pe_layout;
 
 typedef struct pe_cache_desc {
@@ -262,6 +261,8 @@ int pe_append_kv(const pe_cache_desc* desc, const void* new_k, const void* new_v
  * to seq_lens_out [S], which must not alias seq_lens (callers keep two arrays and swap them), so that no
  * workgroup of the launch can observe a length that another one has already bumped.
  * workspace: pe_workspace_bytes(PE_OP_APPEND_PAGED_DECODE, desc, 0).
+ * shared: same contract and shapes as pe_append_kv / pe_paged_decode in that layout, carried out as two launches
+ * (one workgroup per sequence does the page bookkeeping for all heads before the attention reads it).
  */
 int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const void* new_v, const void* q,
                            void* k_pool, void* v_pool, int32_t* block_table, const int32_t* seq_lens,

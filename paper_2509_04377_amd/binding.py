@@ -417,7 +417,7 @@ class PagedCache:
         if self.any_trigger():
             self.score_and_evict()
             self.host_lens = [n - B if (n > 0 and n % B == 0 and n >= self.budget) else n for n in self.host_lens]
-        if fused and not self.shared:   # the one-launch append + attention exists for the per-head layout only
+        if fused:
             self.append_paged_decode(new_k, new_v, q, out, softmax_scale)
         else:
             self.append_kv(new_k, new_v)

@@ -138,7 +138,8 @@ __global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* sco
 }
 
 // Append: one workgroup per sequence.  Phase 1 links a new page into each row when the tail page is
-// full; phase 2 copies the new K/V rows with 16-byte lane accesses.
+// full; phase 2 copies the new K/V rows with 16-byte lane accesses.  The new length goes to seq_lens, or to
+// seq_lens_out when that is given (seq_lens is then only read).
 __global__ __launch_bounds__(kThreads) void append_kv_kernel(const uint4* __restrict__ new_k,
                                                              const uint4* __restrict__ new_v,
                                                              uint4* __restrict__ k_pool, uint4* __restrict__ v_pool,
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(kThreads) void append_kv_kernel(const uint4* __rest
                                                              const int32_t* __restrict__ spare,
                                                              int32_t* __restrict__ spare_used, int n_spare,
                                                              int num_kv_heads, int block_size, int max_blocks,
-                                                             int VEC_PER_ROW) {
+                                                             int VEC_PER_ROW, int32_t* __restrict__ seq_lens_out) {
   const int s = (int)blockIdx.x;
   const int len = seq_lens[s];
   const int slot = len % block_size;
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(kThreads) void append_kv_kernel(const uint4* __rest
     v_pool[dst] = new_v[row * VEC_PER_ROW + u];
   }
   __syncthreads();
-  if (threadIdx.x == 0) seq_lens[s] = len + 1;
+  if (threadIdx.x == 0) (seq_lens_out != nullptr ? seq_lens_out : seq_lens)[s] = len + 1;
 }
 
 }  // namespace
@@ -200,7 +201,7 @@ hipError_t launch_append_kv(const AppendArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL(append_kv_kernel, dim3((unsigned)a.num_seqs), dim3(kThreads), 0, stream, (const uint4*)a.new_k,
                      (const uint4*)a.new_v, (uint4*)a.k_pool, (uint4*)a.v_pool, a.block_table, a.seq_lens,
                      a.freed_phys, a.spare, a.spare_used, a.n_spare, rows_per_seq, a.block_size, a.max_blocks,
-                     vec_per_row);
+                     vec_per_row, a.seq_lens_out);
   return hipGetLastError();
 }
 

@@ -334,8 +334,7 @@ int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const v
     return PE_ERR_INVALID_ARG;
   if (seq_lens_out == seq_lens) return PE_ERR_INVALID_ARG;
   if (n_spare < 1) return PE_ERR_INVALID_ARG;
-  // the heads of a sequence run in different workgroups and would race on the sequence's one table row
-  if (desc->layout != PE_LAYOUT_PER_HEAD) return PE_ERR_UNSUPPORTED;
+
   if (!aligned(k_pool, 16) || !aligned(v_pool, 16) || !aligned(q, 16) || !aligned(new_k, 16) || !aligned(new_v, 16))
     return PE_ERR_INVALID_ARG;
   if (!(softmax_scale == softmax_scale) || softmax_scale - softmax_scale != 0.f) return PE_ERR_INVALID_ARG;
@@ -373,6 +372,34 @@ int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const v
   a.spare_used = spare_used;
   a.seq_lens_out = seq_lens_out;
   a.n_spare = n_spare;
+  if (desc->layout == PE_LAYOUT_SHARED) {
+    // One table row per sequence: the workgroups of a sequence's heads would race on its page bookkeeping
+    // inside one launch, so the same effect is produced by two launches (append, then attention over the
+    // new lengths).
+    pe::AppendArgs ap;
+    ap.new_k = new_k;
+    ap.new_v = new_v;
+    ap.k_pool = k_pool;
+    ap.v_pool = v_pool;
+    ap.block_table = block_table;
+    ap.seq_lens = const_cast<int32_t*>(seq_lens);
+    ap.seq_lens_out = seq_lens_out;
+    ap.freed_phys = freed_phys;
+    ap.spare = spare;
+    ap.spare_used = spare_used;
+    ap.n_spare = n_spare;
+    ap.num_seqs = desc->num_seqs;
+    ap.num_kv_heads = desc->num_kv_heads;
+    ap.head_dim = desc->head_dim;
+    ap.block_size = desc->block_size;
+    ap.max_blocks = desc->max_blocks;
+    ap.is_bf16 = desc->dtype == PE_BF16;
+    ap.shared = true;
+    if (pe::launch_append_kv(ap, static_cast<hipStream_t>(stream)) != hipSuccess) return PE_ERR_HIP;
+    a.seq_lens = seq_lens_out;
+    a.new_k = nullptr;
+    a.new_v = nullptr;
+  }
   return pe::launch_paged_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
 

@@ -61,6 +61,7 @@ struct AppendArgs {
   int n_spare, num_seqs, num_kv_heads, head_dim, block_size, max_blocks;
   bool is_bf16;
   bool shared = false;  // one table row, one spare list and one freed page per sequence
+  int32_t* seq_lens_out = nullptr;  // when set, the new lengths go here and seq_lens is only read
 };
 hipError_t launch_append_kv(const AppendArgs& a, hipStream_t stream);
 

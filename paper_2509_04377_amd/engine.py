@@ -38,7 +38,7 @@ class LayeredCache:
         for l, c in enumerate(self.per_layer):
             c.decode_ws = self.decode_ws
             c.seq_lens_alt = f.seq_lens_alt[l * num_seqs:(l + 1) * num_seqs]
-        self.fused = not shared   # the one-launch append + attention exists for the per-head layout only
+        self.fused = True
         self.host_lens = [0] * num_seqs   # the same in every layer
 
     def prefill_prune_layer(self, layer, k_in, v_in, cu_seqlens, max_seqlen, kept_idx_out=None, workspace=None):

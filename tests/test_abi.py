@@ -79,9 +79,6 @@ def test_shared_layout_host_checks():
     d = _desc(layout=pe.PE_LAYOUT_SHARED)
     L = pe.lib()
     assert L.pe_score_evict(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, 256, None, FAKE, FAKE, None) == pe.PE_ERR_UNSUPPORTED
-    assert L.pe_append_paged_decode(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ctypes.c_void_p(0x2000),
-                                    FAKE, FAKE, FAKE, 4, ctypes.c_float(0.1), FAKE, FAKE, 1 << 30,
-                                    None) == pe.PE_ERR_UNSUPPORTED
     # the shared prune keeps one more score row (the head mean) in its workspace
     per_head = pe.pe_workspace_bytes(pe.PE_OP_PREFILL_PRUNE, _desc(), 4000)
     assert pe.pe_workspace_bytes(pe.PE_OP_PREFILL_PRUNE, d, 4000) >= per_head + 4000 * 4

@@ -207,21 +207,16 @@ def test_shared_prefill_prune(dt, D, Hk, C, B, ties):
     assert np.array_equal(f32(vpd).view(np.int32), vp.view(np.int32))
 
 
-def test_shared_layout_refuses_per_head_only_calls():
+def test_shared_layout_refuses_the_per_head_only_call():
     desc = _desc(torch.bfloat16, 2, 2, 2, 64, 16, 4, 16)
     z = lambda *shape, dt=torch.int32: torch.zeros(shape, dtype=dt, device=DEV)
     kp = z(16, 16, 2, 64, dt=torch.bfloat16)
     with pytest.raises(pe.PeError) as e:
         pe.pe_score_evict(desc, kp, kp, z(2, 4), z(2), 16, None, z(2), z(2))
     assert e.value.status == pe.PE_ERR_UNSUPPORTED
-    x = z(2, 2, 64, dt=torch.bfloat16)
-    with pytest.raises(pe.PeError) as e:
-        pe.pe_append_paged_decode(desc, x, x, x, kp, kp, z(2, 4), z(2), z(2), z(2), z(2, 1), z(2), 0.125,
-                                  torch.empty_like(x), None)
-    assert e.value.status == pe.PE_ERR_UNSUPPORTED
 
 
-def run_shared_loop(wl, steps, layer=0, cached_scores=False, policy=0, protect_first=0, protect_last=0):
+def run_shared_loop(wl, steps, layer=0, cached_scores=False, policy=0, protect_first=0, protect_last=0, fused=True):
     lens = synth.context_lengths(wl, SEED)
     k_in, v_in, cu = synth.prompt_kv(wl, layer, lens, SEED)
     layout = synth.page_layout(wl, lens, SEED, steps=steps, shared=True)
@@ -248,7 +243,7 @@ def run_shared_loop(wl, steps, layer=0, cached_scores=False, policy=0, protect_f
         nk, nv, q = synth.decode_inputs(wl, layer, step, SEED)
         want, oscores, oev, ofr = osh.decode_step(oc, f32(nk), f32(nv), f32(q), None, policy, protect_first, protect_last)
         gc.evicted_logical.fill_(-1)
-        gc.decode_step(nk.to(DEV), nv.to(DEV), q.to(DEV), out)
+        gc.decode_step(nk.to(DEV), nv.to(DEV), q.to(DEV), out, fused=fused)   # fused: the combined C call
         torch.cuda.synchronize()
         where = "step %d" % step
         assert np.array_equal(gc.block_table.cpu().numpy(), oc.block_table), where
@@ -269,6 +264,7 @@ def run_shared_loop(wl, steps, layer=0, cached_scores=False, policy=0, protect_f
     (synth.TINY.with_(num_kv_heads=32, num_q_heads=32, num_seqs=2), 20, 2, {}),      # many heads, no grouping
     (synth.TINY.with_(context=(40,), budget=64), 60, 3, {}),
     (synth.LLAMA32_1B.with_(budget=512, num_seqs=4), 36, 3, {}),
+    (synth.LLAMA32_1B.with_(budget=512, num_seqs=4), 36, 3, dict(fused=False)),
     (synth.LLAMA32_1B.with_(budget=512, num_seqs=4), 36, 3, dict(cached_scores=True)),
     (synth.LLAMA32_3B.with_(num_seqs=3), 20, 2, dict(policy=0, protect_first=1, protect_last=2)),
     (synth.LLAMA31_8B.with_(num_seqs=4, budget=1024), 20, 2, dict(policy=1, protect_first=1)),
