@@ -147,12 +147,13 @@ def test_staggered_triggers(kw):
     assert n_ev >= 8          # many more trigger steps than the 4 a lockstep batch would see in 60 steps
 
 
-@pytest.mark.parametrize("B,fused_evict", [(64, False), (128, False), (64, True)])
-def test_larger_pages(B, fused_evict):
+@pytest.mark.parametrize("B,kw", [(64, {}), (128, {}), (64, dict(fused_evict=True)), (64, dict(cached_scores=True)),
+                                  (128, dict(cached_scores=True, fused=False))])
+def test_larger_pages(B, kw):
     """Pages of 64 and 128 tokens (the method is stated for any page size): the whole loop against the oracle."""
-    print("case loop larger pages", B, fused_evict, flush=True)
+    print("case loop larger pages", B, kw, flush=True)
     wl = synth.LLAMA32_1B.with_(block_size=B, budget=1024, num_seqs=4)
-    n_ev, _ = run_loop(wl, 2 * B + 3, fused_evict=fused_evict)
+    n_ev, _ = run_loop(wl, 2 * B + 3, **kw)
     assert n_ev == 3
 
 

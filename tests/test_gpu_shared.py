@@ -267,6 +267,7 @@ def run_shared_loop(wl, steps, layer=0, cached_scores=False, policy=0, protect_f
     (synth.LLAMA32_1B.with_(budget=512, num_seqs=4), 36, 3, dict(fused=False)),
     (synth.LLAMA32_1B.with_(budget=512, num_seqs=4), 36, 3, dict(cached_scores=True)),
     (synth.LLAMA32_3B.with_(num_seqs=3), 20, 2, dict(policy=0, protect_first=1, protect_last=2)),
+    (synth.LLAMA32_3B.with_(num_seqs=3, block_size=64), 70, 2, dict(cached_scores=True)),
     (synth.LLAMA31_8B.with_(num_seqs=4, budget=1024), 20, 2, dict(policy=1, protect_first=1)),
 ])
 def test_shared_decode_loop(wl, steps, n_want, kw):
