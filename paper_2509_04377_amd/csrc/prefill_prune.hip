@@ -152,6 +152,7 @@ __global__ __launch_bounds__(kThreads) void head_mean_kernel(const float* __rest
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kSelBins = 4096;
+constexpr int kSelUnroll = 8;
 
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores,
                                                              const int32_t* __restrict__ cu_seqlens,
@@ -192,9 +193,19 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     const int per_thread = nbins / kSelThreads;  // 4 or 1 consecutive bins per thread
     for (int i = tid; i < nbins; i += kSelThreads) hist[i] = 0u;
     __syncthreads();
-    for (int i = tid; i < L; i += kSelThreads) {
-      const uint32_t b = bits[i];
-      if ((b & mask) == prefix) atomicAdd(&hist[(b >> shift) & (uint32_t)(nbins - 1)], 1u);
+    // eight loads in flight per thread: the LDS atomics would otherwise serialise the loop on load latency
+    for (int base = tid; base < L; base += kSelUnroll * kSelThreads) {
+      uint32_t b[kSelUnroll];
+#pragma unroll
+      for (int j = 0; j < kSelUnroll; ++j) {
+        const int i = base + j * kSelThreads;
+        b[j] = bits[i < L ? i : L - 1];
+      }
+#pragma unroll
+      for (int j = 0; j < kSelUnroll; ++j) {
+        const int i = base + j * kSelThreads;
+        if (i < L && (b[j] & mask) == prefix) atomicAdd(&hist[(b[j] >> shift) & (uint32_t)(nbins - 1)], 1u);
+      }
     }
     __syncthreads();
     // workgroup-wide exclusive scan of the per-thread bin totals, in bin order
