@@ -12,7 +12,8 @@
  * Granularity: every decision is taken per ROW = one (sequence, KV head).  A row owns one row of the
  * block table and its own pages; a page holds B x D elements of K (and a sibling page of V, same
  * physical index in v_pool) of ONE KV head.  Layers are independent: for (1), (2) a caller may fold
- * layers into the sequence dimension.
+ * layers into the sequence dimension.  (This is desc->layout == PE_LAYOUT_PER_HEAD, the default; pe_layout
+ * below describes the head-shared alternative and each call states what changes under it.)
  *
  * Conventions that hold for every call below:
  *   - Every pointer except `desc` is a DEVICE pointer owned by the caller.  The library never
@@ -20,7 +21,8 @@
  *     stream).  A call enqueues its kernels on `stream` and returns a host-side status at once.
  *   - Tensors are dense, row-major, in the shapes given; K/V/q/out element type is desc->dtype
  *     (PE_F32: IEEE binary32, PE_BF16: bfloat16); tables and lengths are int32.
- *   - Pools: [num_phys_blocks][block_size][head_dim]; page p starts at element p*B*D.
+ *   - Pools: [num_phys_blocks][block_size][head_dim]; page p starts at element p*B*D (head-shared layout:
+ *     [num_phys_blocks][block_size][num_kv_heads][head_dim]).
  *   - block_table: [num_seqs][num_kv_heads][max_blocks]; entry j of a row is the physical page of its
  *     logical page j; entries at and beyond ceil(len/B) are -1.  seq_lens: [num_seqs] cached tokens
  *     (the same for all KV heads of a sequence).
