@@ -292,3 +292,64 @@ def test_full_size_one_layer_and_determinism(wl):
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
     e2, emax = rel_err(f32(o1), f32(out[l]).astype(np.float64))
     assert e2 <= 2e-2 and emax <= 2e-2
+
+
+@pytest.mark.parametrize("shared,stagger", [(False, False), (False, True), (True, False), (True, True)])
+def test_all_driver_modes_agree_at_full_size(shared, stagger):
+    """The whole headline job (32 layers x 32 sequences x 8 KV heads at budget 2048, one shared shuffled pool)
+    stepped 36 times in every mode of the layered driver: the paper's procedure, cached scores, one-launch
+    score+evict, separate append launches, HIP-graph replay.  Every mode must end with the same block tables,
+    lengths and spare counters, bit for bit (the decisions are the same decisions), and the same attention
+    outputs within the bf16 tolerance (the fused and the separate attention sum in different orders).  Also in
+    the head-shared layout (which has no one-launch score+evict), and with prompts just under the budget so that
+    the sequences evict at different steps."""
+    from paper_2509_04377_amd.engine import GraphedStepper
+    print("case loop modes agree", shared, stagger, flush=True)
+    wl = synth.LLAMA31_8B
+    L, S, Hk, Hq, D, B, C = wl.layers, wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim, wl.block_size, wl.budget
+    lens = [C - (i % B) for i in range(S)] if stagger else [C] * S
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=DEV)
+    steps = 36
+    g = torch.Generator(device=DEV)
+    g.manual_seed(SEED + 7)
+    nk = torch.randn((4, L, S, Hk, D), generator=g, device=DEV).to(wl.torch_dtype)
+    nv = torch.randn((4, L, S, Hk, D), generator=g, device=DEV).to(wl.torch_dtype)
+    q = torch.randn((4, L, S, Hq, D), generator=g, device=DEV).to(wl.torch_dtype)
+    ref = None
+    for mode in ("paper", "cached", "fused_evict", "unfused", "graph"):
+        if shared and mode == "fused_evict":
+            continue
+        layout = synth.page_layout(wl, lens * L, SEED, steps=steps, shared=shared)
+        eng = LayeredCache(wl.torch_dtype, L, S, Hk, Hq, D, B, layout, C, DEV, shared=shared)
+        for l in range(L):
+            k_in, v_in, _ = synth.prompt_kv(wl, l, lens, SEED, device=DEV)
+            eng.prefill_prune_layer(l, k_in, v_in, cu, max(lens))
+            del k_in, v_in
+        eng.set_host_lens(lens)
+        eng.folded.cached_scores = mode == "cached"
+        eng.folded.fused_evict = mode == "fused_evict"
+        eng.fused = mode != "unfused"
+        out = torch.zeros((L, S, Hq, D), dtype=wl.torch_dtype, device=DEV)
+        n_trig = 0
+        if mode == "graph":
+            bufs = (nk[0].clone(), nv[0].clone(), q[0].clone())
+            stepper = GraphedStepper(eng, bufs[0], bufs[1], bufs[2], out)
+        for st in range(steps):
+            i = st % 4
+            if mode == "graph":
+                bufs[0].copy_(nk[i]); bufs[1].copy_(nv[i]); bufs[2].copy_(q[i])
+                n_trig += bool(stepper.step())
+            else:
+                n_trig += bool(eng.decode_step(nk[i], nv[i], q[i], out))
+        torch.cuda.synchronize()
+        assert n_trig == (steps if stagger else 3)
+        state = (eng.folded.block_table.clone(), eng.folded.seq_lens.clone(), eng.folded.spare_used.clone(),
+                 out.float().cpu().numpy())
+        if ref is None:
+            ref = state
+        else:
+            assert torch.equal(state[0], ref[0]) and torch.equal(state[1], ref[1]) and torch.equal(state[2], ref[2]), mode
+            e2, emax = rel_err(state[3].reshape(-1, D), ref[3].reshape(-1, D).astype(np.float64))
+            assert e2 <= 2e-2 and emax <= 2e-2, (mode, e2, emax)
+        del eng, layout, out
+        torch.cuda.empty_cache()
