@@ -198,11 +198,13 @@ def kernel_breakdown(eng, wl, new_k, new_v, q, out):
     med = lambda v: v[len(v) // 2]
     return {"note": "one trigger step issued call by call after the timed region; event-to-event times, each "
                     "includes its launch gap",
-            "score_blocks": {"us": score_us, "bytes": score_bytes, "GBps": score_bytes / score_us / 1e3},
+            "score_blocks": {"us": score_us, "bytes": score_bytes, "GBps": score_bytes / score_us / 1e3,
+                             "frac_of_hbm_peak": score_bytes / score_us / 1e3 / HBM_PEAK_GBS},
             "evict_blocks": {"us": e1.elapsed_time(e2) * 1e3, "rows": L * S * Hk},
             "append_kv": {"us_median_per_layer": med(app)},
             "paged_decode": {"us_median_per_layer": med(att), "bytes": att_bytes,
-                             "GBps": att_bytes / med(att) / 1e3}}
+                             "GBps": att_bytes / med(att) / 1e3,
+                             "frac_of_hbm_peak": att_bytes / med(att) / 1e3 / HBM_PEAK_GBS}}
 
 
 def main():
@@ -334,8 +336,11 @@ def main():
                    "trigger_steps": n_trigger, "sequence_evictions": n_trigger_seqs},
         "step_ms": {"p50": step_ms[len(step_ms) // 2], "p99": step_ms[min(len(step_ms) - 1, int(len(step_ms) * 0.99))],
                     "max": step_ms[-1]},
+        # host-timed per layer (four launches and a synchronisation), against the K/V bytes the sweep reads
         "prefill_prune": {"ms_per_layer": sorted(prune_ms)[len(prune_ms) // 2],
-                          "sweep_GBps": prune_bytes / (sorted(prune_ms)[len(prune_ms) // 2] * 1e-3) / 1e9},
+                          "sweep_GBps": prune_bytes / (sorted(prune_ms)[len(prune_ms) // 2] * 1e-3) / 1e9,
+                          "sweep_frac_of_hbm_peak": prune_bytes / (sorted(prune_ms)[len(prune_ms) // 2] * 1e-3) / 1e9
+                          / HBM_PEAK_GBS},
     }
     result["roofline"] = None   # stays None when no step could be sampled (graph replay of trigger-only runs)
     if samples:
