@@ -298,6 +298,7 @@ def main():
             e.record()
             samples.append((state["e0"], e, 1, per_launch))
 
+    sample_every = min(args.sample_every, args.steps)   # a short run still times the launches of one step
     step_events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     n_trigger = 0        # steps on which some sequence evicts
     n_trigger_seqs = 0   # sequence-evictions over the timed region (each scores its own pages)
@@ -306,7 +307,7 @@ def main():
     step_events[0].record()
     for st in range(args.steps):
         i = (args.warmup + st) % ring
-        sampled = args.sample_every > 0 and st % args.sample_every == args.sample_every // 2
+        sampled = sample_every > 0 and st % sample_every == sample_every // 2
         n_trigger_seqs += sum(eng._triggers())
         if stepper is not None:
             trig = stepper.step()
