@@ -117,6 +117,16 @@ def test_many_kv_heads_without_grouping():
     assert n_ev == 2
 
 
+@pytest.mark.parametrize("fused", [True, False])
+def test_budget_of_one_page(fused):
+    """The smallest budget there is, C = B: every eviction drops the row's only page, the cache restarts from
+    the new token alone and the freed page is taken again at once."""
+    print("case loop one-page budget", fused, flush=True)
+    wl = synth.TINY.with_(context=(40,), budget=16, num_seqs=2)
+    n_ev, _ = run_loop(wl, 35, fused=fused)
+    assert n_ev == 3          # steps 0, 16, 32
+
+
 def test_tiny_under_budget_growth():
     print("case loop tiny under budget", flush=True)
     wl = synth.TINY.with_(context=(40,), budget=64)

@@ -140,3 +140,20 @@ def test_append_consumes_the_freed_page_once():
     assert table[0, 0, 2] == spare[0, 0, 0] and table[0, 1, 2] == spare[0, 1, 1]
     assert used[0].tolist() == [1, 2] and np.all(freed == -1)
     assert lens.tolist() == [2 * B + 1, 5 + B + 1] and table[1, 0, 1] == spare[1, 0, 0]
+
+
+def test_budget_of_one_page_restarts_from_the_new_token():
+    """C = B: each eviction drops the row's only page, so right after it the cache holds the new token alone
+    and its attention output is that token's V row; the shadow model checks every other step."""
+    wl = synth.TINY.with_(context=(40,), budget=16)
+    cache, history, _ = _run(wl, 16, 35)
+    trig = [i for i, (_, _, ev, _) in enumerate(history) if (ev >= 0).any()]
+    assert trig == [0, 16, 32]
+    for i in trig:
+        len_before, len_after, ev, out = history[i]
+        assert len_before[0] == 16 and len_after[0] == 1 and np.all(ev == 0)
+        nk, nv, q = (f32(x) for x in synth.decode_inputs(wl, 0, i, SEED))
+        G = wl.num_q_heads // wl.num_kv_heads
+        for hq in range(wl.num_q_heads):
+            np.testing.assert_allclose(out[0, hq], nv[0, hq // G].astype(np.float64), rtol=1e-12)
+    assert np.all(cache.spare_used == 0)        # the freed page is reused every time
