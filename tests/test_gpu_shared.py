@@ -263,6 +263,7 @@ def run_shared_loop(wl, steps, layer=0, cached_scores=False, policy=0, protect_f
     (synth.TINY, 40, 3, {}),
     (synth.TINY.with_(num_kv_heads=32, num_q_heads=32, num_seqs=2), 20, 2, {}),      # many heads, no grouping
     (synth.TINY.with_(context=(40,), budget=64), 60, 3, {}),
+    (synth.TINY.with_(context=(40,), budget=16, num_seqs=2), 35, 3, {}),             # one-page budget
     (synth.LLAMA32_1B.with_(budget=512, num_seqs=4), 36, 3, {}),
     (synth.LLAMA32_1B.with_(budget=512, num_seqs=4), 36, 3, dict(fused=False)),
     (synth.LLAMA32_1B.with_(budget=512, num_seqs=4), 36, 3, dict(cached_scores=True)),
