@@ -78,7 +78,7 @@ def traffic_from_profiles(workload):
     return None
 
 
-def build_engine(wl, seed, dev, shared=False, stagger=False):
+def build_engine(wl, seed, dev, shared=False, stagger=False, decode_opts=None):
     import torch
     from paper_2509_04377_amd import binding as pe
     from paper_2509_04377_amd import synth
@@ -89,7 +89,7 @@ def build_engine(wl, seed, dev, shared=False, stagger=False):
         lens = [wl.budget - (s % wl.block_size) for s in range(wl.num_seqs)]
     layout = synth.page_layout(wl, lens * wl.layers, seed, shared=shared)
     eng = LayeredCache(wl.torch_dtype, wl.layers, wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim,
-                       wl.block_size, layout, wl.budget, dev, shared=shared)
+                       wl.block_size, layout, wl.budget, dev, shared=shared, decode_opts=decode_opts)
     total = sum(lens)
     ws = pe.alloc_workspace(pe.PE_OP_PREFILL_PRUNE, eng.per_layer[0].desc, total, device=dev)
     prune_ms = []
@@ -226,23 +226,20 @@ def main():
         wl = wl.with_(num_q_heads=args.q_heads)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    decode_opts = {}
     if args.splits is not None:
-        pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, args.splits)
+        decode_opts["decode_splits"] = args.splits
     if args.xcd_map is not None:
-        pe.pe_set_option(pe.PE_OPT_DECODE_XCD_MAP, args.xcd_map)
-    if args.waves is not None:
-        pe.pe_set_option(pe.PE_OPT_DECODE_WAVES, args.waves)
-    if args.depth is not None:
-        pe.pe_set_option(pe.PE_OPT_DECODE_DEPTH, args.depth)
-    if args.loads is not None:
-        pe.pe_set_option(pe.PE_OPT_DECODE_LOADS, args.loads)
+        decode_opts["decode_flat_order"] = 1 - args.xcd_map
+    if args.waves is not None or args.depth is not None or args.loads is not None:
+        decode_opts["decode_shape"] = (args.waves or 4) * 100 + (args.depth or 2) * 10 + (args.loads or 2)
 
     shared = args.layout == "shared"
     # the committed counter summary covers the workload as defined, in the per-head layout; any override of the
     # shape changes the bytes, so no measured traffic is quoted then
     overridden = any(v is not None for v in (args.budget, args.block_size, args.q_heads)) or args.stagger
     profile_key = None if overridden else wl.name + ("_shared" if shared else "")
-    eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev, shared, args.stagger)
+    eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev, shared, args.stagger, decode_opts)
     # shared layout: the combined call is two launches inside the library; issue them separately here so that the
     # events bracket the attention kernel alone
     eng.fused = not args.unfused and not shared
@@ -333,7 +330,7 @@ def main():
         "config": {"workload": "%s: %d layers, %d seqs x %d KV heads (%d q heads), head_dim %d, page %d, context %s -> "
                                "budget %d" % (wl.name, L, S, Hk, Hq, D, wl.block_size, "/".join(map(str, wl.context)),
                                               wl.budget),
-                   "layout": args.layout, "stagger": args.stagger, "decode_splits": pe.pe_get_option(pe.PE_OPT_DECODE_SPLITS), "fused_append": eng.fused, "cached_scores": args.cached_scores, "fused_evict": args.fused_evict, "hip_graph": args.graph,
+                   "layout": args.layout, "stagger": args.stagger, "decode_splits": pe.pe_decode_splits(eng.per_layer[0].desc), "fused_append": eng.fused, "cached_scores": args.cached_scores, "fused_evict": args.fused_evict, "hip_graph": args.graph,
                    "trigger_steps": n_trigger, "sequence_evictions": n_trigger_seqs},
         "step_ms": {"p50": step_ms[len(step_ms) // 2], "p99": step_ms[min(len(step_ms) - 1, int(len(step_ms) * 0.99))],
                     "max": step_ms[-1]},

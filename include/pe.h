@@ -81,11 +81,20 @@ typedef struct pe_cache_desc {
   int32_t max_blocks;      /* row stride of block_table and of the score array */
   int64_t num_phys_blocks; /* P: pages in each pool */
   int32_t layout;          /* pe_layout; 0 when the struct is zero- or positionally initialised up to P */
+  /* Launch shape of the attention calls (4).  All zero = the library's choice; a caller that tunes sets them
+   * per descriptor, so two callers in one process never interfere, and pe_workspace_bytes(), pe_decode_splits()
+   * and the launch read the same fields and agree by construction. */
+  int32_t decode_splits;   /* 0: chosen from the shape and the device's compute-unit count; 1..256: that many
+                              splits of every row (1 = no partials, no workspace) */
+  int32_t decode_shape;    /* 0: default; else waves*100 + buffers*10 + loads of the attention workgroup.  Built:
+                              422 (default), 424, 432, 822, and only for bf16, D = 128, Hq/Hk = 4, per-head layout;
+                              anything else returns PE_ERR_UNSUPPORTED from the attention calls */
+  int32_t decode_flat_order; /* 0: workgroup order that keeps the splits of a row on one XCD; 1: plain row-major */
 } pe_cache_desc;
 
 /* Bytes of device workspace `op` needs for `desc`.  `total_tokens` is the packed prompt length
  * (sum of L) for PE_OP_PREFILL_PRUNE and ignored otherwise.  Returns 0 for ops that need none and
- * for an invalid desc. */
+ * for an invalid desc.  For the attention ops the size follows pe_decode_splits(desc). */
 size_t pe_workspace_bytes(int op, const pe_cache_desc* desc, int64_t total_tokens);
 
 /* Static string for a pe_status value. */
@@ -94,17 +103,11 @@ const char* pe_status_string(int status);
 /* ABI version: major*10000 + minor*100 + patch. */
 int pe_version(void);
 
-/* Tuning knobs (host side, process wide, not thread safe).  PE_OPT_DECODE_SPLITS: number of splits of a
- * row in pe_paged_decode (0 = choose from the shape); pe_workspace_bytes() follows the current setting.
- * PE_OPT_DECODE_XCD_MAP: 1 = workgroup order that keeps the splits of a row on one XCD.
- * PE_OPT_DECODE_WAVES / _DEPTH / _LOADS: waves per workgroup (4, 8), register buffers (2, 3) and wave-loads
- * per tile (2, 4) of the decode kernel; only the bf16, head_dim 128, group 4 instantiation honours values
- * other than the defaults 4 / 2 / 2 (an unsupported combination makes the decode call return PE_ERR_HIP).
- * Returns PE_OK or PE_ERR_INVALID_ARG. */
-enum { PE_OPT_DECODE_SPLITS = 0, PE_OPT_DECODE_XCD_MAP = 1, PE_OPT_DECODE_WAVES = 2, PE_OPT_DECODE_DEPTH = 3,
-       PE_OPT_DECODE_LOADS = 4, PE_OPT_COUNT_ = 5 };
-int pe_set_option(int key, int value);
-int pe_get_option(int key);
+/* Number of splits of a row the attention calls (4) use for `desc` on the current device: desc->decode_splits
+ * when that is set, else enough splits to give every compute unit of the device one workgroup, never shorter
+ * than 256 tokens each.  0 for an invalid desc.  (The compute-unit count is read from the HIP runtime once per
+ * device; without a device it is taken as 256, an MI355X.) */
+int pe_decode_splits(const pe_cache_desc* desc);
 
 /*
  * (1) Block scores -- Alg. 1 (block mode), used by Alg. 3 "Compute Score of Page i"; Sec. 4.3.
@@ -132,7 +135,8 @@ int pe_score_blocks(const pe_cache_desc* desc, const void* k_pool, const void* v
  *     max_seqlen: an upper bound on every L_s (host value, sizes the launch).
  *     budget_tokens: C, a positive multiple of B.
  *     block_table is an INPUT: the caller has put ceil(min(L_s, C)/B) distinct physical pages in each
- *     row.  Slots of the tail page past the kept count are left untouched.
+ *     row (ceil(min(max_seqlen, C)/B) > max_blocks is refused with PE_ERR_INVALID_ARG).  Slots of the tail
+ *     page past the kept count are left untouched.
  *     kept_idx_out: NULL, or [S][Hk][budget_tokens] int32 that receives the in-sequence indices of the
  *     kept tokens in ascending order, -1 padded.
  *     workspace: pe_workspace_bytes(PE_OP_PREFILL_PRUNE, desc, total_tokens).
@@ -154,7 +158,10 @@ int pe_prefill_prune(const pe_cache_desc* desc, const void* k_in, const void* v_
  *     entry.  evicted_logical_out / freed_phys_out [S][Hk] receive j* / the physical page that was
  *     removed, or -1 for rows that did not evict.  seq_lens[s] -= B, once per triggering sequence.
  *     Exactly one page per row per call.  scores: [S][Hk][max_blocks] fp32 (e.g. from (1)); compared
- *     as fp32 values.  block_table and seq_lens are updated in place.
+ *     as fp32 values.  A NaN score never compares lower than another; if every candidate of a row is NaN
+ *     (finite K/V never produce one) the row's first candidate page goes, so the call stays inside the row.
+ *     block_table and seq_lens are updated in place.  A budget beyond the row capacity max_blocks*B never
+ *     triggers.
  *     shared: the sequence's one table row [S][max_blocks] drops the page with the lowest head-mean score
  *     (scores stays [S][Hk][max_blocks]); evicted_logical_out / freed_phys_out are [S].  The same holds for
  *     the variants below (share_heads is then implied).
@@ -182,7 +189,9 @@ int pe_evict_blocks_cached(const pe_cache_desc* desc, float* scores_inout, int32
 
 /*
  * (1) restricted to the sequences that (3) will act on: Alg. 3 scores pages only inside its "L % B == 0"
- * branch, i.e. for a sequence whose newest page has just filled (and, reading G3, which is at budget).
+ * branch, i.e. for a sequence whose newest page has just filled and which is at budget.  (Alg. 3 lists the
+ * budget C among its inputs but its printed trigger is only "L % B == 0"; here and in (3) the trigger is gated on
+ * seq_lens[s] >= C, so that a budget >= context reproduces full attention: Sec. 4.3, Alg. 3.)
  * Rows of sequences that do not trigger at `budget_tokens` are neither read nor written (their entries of
  * scores_inout keep whatever they held); rows of triggering sequences are written exactly as by (1).  With
  * sequences that reach a page boundary at different steps this reads a fraction of what (1) reads.

@@ -52,8 +52,10 @@ __global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* sco
   // the KV heads in fp64, head order, one rounding to fp32) BEFORE any wave touches a score row.
   int j_shared = lo;
   if (trigger && policy == 0 && share_heads) {
+    // the search starts from (+inf, lo): a NaN never compares lower, so a row whose candidates are all NaN (a
+    // precondition violation: K/V must be finite) still ends with an index inside [lo, hi)
     float best = __builtin_inff();
-    int best_j = 0x7fffffff;
+    int best_j = lo;
     for (int j = lo + lane; j < hi; j += kWave) {
       double sum = 0.0;
       for (int g = 0; g < num_kv_heads; ++g) sum += (double)scores[((int64_t)s * num_kv_heads + g) * max_blocks + j];
@@ -110,7 +112,7 @@ __global__ __launch_bounds__(kThreads) void evict_blocks_kernel(const float* sco
     if (policy == 0 && !share_heads) {
       const float* sc_row = scores + row * max_blocks;
       float best = __builtin_inff();
-      int best_j = 0x7fffffff;
+      int best_j = lo;  // as above: the result stays inside [lo, hi) whatever the scores hold
       for (int j = lo + lane; j < hi; j += kWave) {
         const float v = sc_row[j];
         if (v < best || (v == best && j < best_j)) {

@@ -2,14 +2,16 @@
 // the caller's stream.  Nothing here allocates, frees or synchronises.
 #include "../../include/pe.h"
 
+#include <atomic>
+
 #include "pe_launch.h"
 
 namespace {
 
-int g_options[PE_OPT_COUNT_] = {0 /* decode splits: auto */, 1 /* XCD-aware workgroup order */, 4 /* waves */,
-                                2 /* pipeline depth */, 2 /* loads per tile */};
-
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// The decode workgroup shapes that are built (waves*100 + register buffers*10 + wave-loads per tile).
+bool decode_shape_built(int shape) { return shape == 422 || shape == 424 || shape == 432 || shape == 822; }
 
 // PE_OK if the descriptor names a shape the kernels are built for.
 int check_desc(const pe_cache_desc* d) {
@@ -25,18 +27,46 @@ int check_desc(const pe_cache_desc* d) {
   if (d->layout != PE_LAYOUT_PER_HEAD && d->layout != PE_LAYOUT_SHARED) return PE_ERR_UNSUPPORTED;
   if (d->num_phys_blocks > 0x7fffffffLL) return PE_ERR_UNSUPPORTED;
   if ((int64_t)d->num_seqs * d->num_kv_heads > 0x7fffffffLL / 64) return PE_ERR_UNSUPPORTED;
+  if (d->decode_splits < 0 || d->decode_splits > 256) return PE_ERR_INVALID_ARG;
+  if (d->decode_flat_order != 0 && d->decode_flat_order != 1) return PE_ERR_INVALID_ARG;
+  if (d->decode_shape != 0) {
+    if (!decode_shape_built(d->decode_shape)) return PE_ERR_UNSUPPORTED;
+    const bool tunable = d->dtype == PE_BF16 && d->head_dim == 128 && d->num_q_heads / d->num_kv_heads == 4 &&
+                         d->layout == PE_LAYOUT_PER_HEAD;
+    if (d->decode_shape != 422 && !tunable) return PE_ERR_UNSUPPORTED;
+  }
   return PE_OK;
 }
 
-// Number of splits of a row in pe_paged_decode.  The kernel streams best with ONE four-wave workgroup per
+// Compute units of the current device, asked of the HIP runtime once per device.  Without a device (or on an
+// error) the count of an MI355X is assumed; the sticky error state of the runtime is left clean.
+int compute_units() {
+  constexpr int kMaxDevices = 64, kDefault = 256;
+  static std::atomic<int> cached[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return kDefault;
+  }
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+    (void)hipGetLastError();
+    return kDefault;
+  }
+  cached[dev].store(n, std::memory_order_relaxed);
+  return n;
+}
+
+// Number of splits of a row in the attention calls.  The kernel streams best with ONE four-wave workgroup per
 // compute unit (each wave keeps a tile in flight while it consumes another; more resident workgroups only
-// add prologue, epilogue and merge work), so rows are split just enough to cover the 256 compute units of
-// an MI355X, and never into splits shorter than 256 tokens.
+// add prologue, epilogue and merge work), so rows are split just enough to cover the compute units of the
+// device, and never into splits shorter than 256 tokens.
 int decode_splits(const pe_cache_desc* d) {
-  if (g_options[PE_OPT_DECODE_SPLITS] > 0) return g_options[PE_OPT_DECODE_SPLITS];
+  if (d->decode_splits > 0) return d->decode_splits;
   const int64_t rows = (int64_t)d->num_seqs * d->num_kv_heads;
-  const int64_t compute_units = 256;
-  int64_t splits = (compute_units + rows - 1) / rows;
+  const int64_t cus = compute_units();
+  int64_t splits = (cus + rows - 1) / rows;
   const int64_t max_tokens = (int64_t)d->max_blocks * d->block_size;
   const int64_t max_by_len = max_tokens / 256 > 1 ? max_tokens / 256 : 1;
   if (splits > max_by_len) splits = max_by_len;
@@ -51,11 +81,33 @@ int check_workspace(const void* ws, size_t have, size_t need) {
   return PE_OK;
 }
 
+bool finite(float x) { return x == x && x - x == 0.f; }
+
+// The part of the attention launch description that follows from the descriptor alone.
+pe::DecodeArgs decode_args(const pe_cache_desc* desc, int splits) {
+  pe::DecodeArgs a;
+  a.num_seqs = desc->num_seqs;
+  a.num_kv_heads = desc->num_kv_heads;
+  a.num_q_heads = desc->num_q_heads;
+  a.head_dim = desc->head_dim;
+  a.block_size = desc->block_size;
+  a.max_blocks = desc->max_blocks;
+  a.splits = splits;
+  a.xcd_map = desc->decode_flat_order ? 0 : 1;
+  const int shape = desc->decode_shape != 0 ? desc->decode_shape : 422;
+  a.waves = shape / 100;
+  a.depth = shape / 10 % 10;
+  a.loads = shape % 10;
+  a.is_bf16 = desc->dtype == PE_BF16;
+  a.shared = desc->layout == PE_LAYOUT_SHARED;
+  return a;
+}
+
 }  // namespace
 
 extern "C" {
 
-int pe_version(void) { return 200; }  // 0.2.0: pe_cache_desc gained `layout`
+int pe_version(void) { return 300; }  // 0.3.0: per-descriptor launch shape replaces the process-wide options
 
 const char* pe_status_string(int status) {
   switch (status) {
@@ -68,21 +120,7 @@ const char* pe_status_string(int status) {
   }
 }
 
-int pe_set_option(int key, int value) {
-  if (key < 0 || key >= PE_OPT_COUNT_) return PE_ERR_INVALID_ARG;
-  if (key == PE_OPT_DECODE_SPLITS && (value < 0 || value > 256)) return PE_ERR_INVALID_ARG;
-  if (key == PE_OPT_DECODE_XCD_MAP && value != 0 && value != 1) return PE_ERR_INVALID_ARG;
-  if (key == PE_OPT_DECODE_WAVES && value != 4 && value != 8) return PE_ERR_INVALID_ARG;
-  if (key == PE_OPT_DECODE_DEPTH && (value < 2 || value > 3)) return PE_ERR_INVALID_ARG;
-  if (key == PE_OPT_DECODE_LOADS && value != 2 && value != 4) return PE_ERR_INVALID_ARG;
-  g_options[key] = value;
-  return PE_OK;
-}
-
-int pe_get_option(int key) {
-  if (key < 0 || key >= PE_OPT_COUNT_) return PE_ERR_INVALID_ARG;
-  return g_options[key];
-}
+int pe_decode_splits(const pe_cache_desc* desc) { return check_desc(desc) == PE_OK ? decode_splits(desc) : 0; }
 
 size_t pe_workspace_bytes(int op, const pe_cache_desc* desc, int64_t total_tokens) {
   if (check_desc(desc) != PE_OK) return 0;
@@ -165,6 +203,10 @@ int pe_prefill_prune(const pe_cache_desc* desc, const void* k_in, const void* v_
     return PE_ERR_INVALID_ARG;
   if (total_tokens > 0 && (!k_in || !v_in)) return PE_ERR_INVALID_ARG;
   if (budget_tokens <= 0 || budget_tokens % desc->block_size != 0) return PE_ERR_INVALID_ARG;
+  {  // the longest pruned row must fit a table row: the gather indexes block_table[...][pos / B]
+    const int64_t keep = max_seqlen < budget_tokens ? max_seqlen : budget_tokens;
+    if ((keep + desc->block_size - 1) / desc->block_size > desc->max_blocks) return PE_ERR_INVALID_ARG;
+  }
   if (!aligned(k_pool, 16) || !aligned(v_pool, 16) || !aligned(k_in, 16) || !aligned(v_in, 16))
     return PE_ERR_INVALID_ARG;
   const int ws = check_workspace(workspace, workspace_bytes,
@@ -291,13 +333,13 @@ int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool
   if (st != PE_OK) return st;
   if (!q || !k_pool || !v_pool || !block_table || !seq_lens || !out) return PE_ERR_INVALID_ARG;
   if (!aligned(k_pool, 16) || !aligned(v_pool, 16) || !aligned(q, 16)) return PE_ERR_INVALID_ARG;
-  if (!(softmax_scale == softmax_scale) || softmax_scale - softmax_scale != 0.f) return PE_ERR_INVALID_ARG;
+  if (!finite(softmax_scale)) return PE_ERR_INVALID_ARG;
   const int splits = decode_splits(desc);
   const int ws = check_workspace(
       workspace, workspace_bytes,
       pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, splits));
   if (ws != PE_OK) return ws;
-  pe::DecodeArgs a;
+  pe::DecodeArgs a = decode_args(desc, splits);
   a.q = q;
   a.k_pool = k_pool;
   a.v_pool = v_pool;
@@ -306,19 +348,6 @@ int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool
   a.out = out;
   a.partials = static_cast<float*>(workspace);
   a.scale = softmax_scale;
-  a.num_seqs = desc->num_seqs;
-  a.num_kv_heads = desc->num_kv_heads;
-  a.num_q_heads = desc->num_q_heads;
-  a.head_dim = desc->head_dim;
-  a.block_size = desc->block_size;
-  a.max_blocks = desc->max_blocks;
-  a.splits = splits;
-  a.xcd_map = g_options[PE_OPT_DECODE_XCD_MAP];
-  a.waves = g_options[PE_OPT_DECODE_WAVES];
-  a.depth = g_options[PE_OPT_DECODE_DEPTH];
-  a.loads = g_options[PE_OPT_DECODE_LOADS];
-  a.is_bf16 = desc->dtype == PE_BF16;
-  a.shared = desc->layout == PE_LAYOUT_SHARED;
   return pe::launch_paged_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
 
@@ -334,16 +363,15 @@ int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const v
     return PE_ERR_INVALID_ARG;
   if (seq_lens_out == seq_lens) return PE_ERR_INVALID_ARG;
   if (n_spare < 1) return PE_ERR_INVALID_ARG;
-
   if (!aligned(k_pool, 16) || !aligned(v_pool, 16) || !aligned(q, 16) || !aligned(new_k, 16) || !aligned(new_v, 16))
     return PE_ERR_INVALID_ARG;
-  if (!(softmax_scale == softmax_scale) || softmax_scale - softmax_scale != 0.f) return PE_ERR_INVALID_ARG;
+  if (!finite(softmax_scale)) return PE_ERR_INVALID_ARG;
   const int splits = decode_splits(desc);
   const int ws = check_workspace(
       workspace, workspace_bytes,
       pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, splits));
   if (ws != PE_OK) return ws;
-  pe::DecodeArgs a;
+  pe::DecodeArgs a = decode_args(desc, splits);
   a.q = q;
   a.k_pool = k_pool;
   a.v_pool = v_pool;
@@ -352,19 +380,6 @@ int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const v
   a.out = out;
   a.partials = static_cast<float*>(workspace);
   a.scale = softmax_scale;
-  a.num_seqs = desc->num_seqs;
-  a.num_kv_heads = desc->num_kv_heads;
-  a.num_q_heads = desc->num_q_heads;
-  a.head_dim = desc->head_dim;
-  a.block_size = desc->block_size;
-  a.max_blocks = desc->max_blocks;
-  a.splits = splits;
-  a.xcd_map = g_options[PE_OPT_DECODE_XCD_MAP];
-  a.waves = g_options[PE_OPT_DECODE_WAVES];
-  a.depth = g_options[PE_OPT_DECODE_DEPTH];
-  a.loads = g_options[PE_OPT_DECODE_LOADS];
-  a.is_bf16 = desc->dtype == PE_BF16;
-  a.shared = desc->layout == PE_LAYOUT_SHARED;
   a.new_k = new_k;
   a.new_v = new_v;
   a.freed_phys = freed_phys;

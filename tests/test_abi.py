@@ -43,7 +43,11 @@ def _desc(**kw):
     (dict(head_dim=96), pe.PE_ERR_UNSUPPORTED), (dict(block_size=8), pe.PE_ERR_UNSUPPORTED),
     (dict(dtype=7), pe.PE_ERR_UNSUPPORTED), (dict(num_q_heads=30), pe.PE_ERR_INVALID_ARG),
     (dict(num_q_heads=128), pe.PE_ERR_UNSUPPORTED), (dict(num_seqs=0), pe.PE_ERR_INVALID_ARG),
-    (dict(max_blocks=0), pe.PE_ERR_INVALID_ARG), (dict(layout=5), pe.PE_ERR_UNSUPPORTED)])
+    (dict(max_blocks=0), pe.PE_ERR_INVALID_ARG), (dict(layout=5), pe.PE_ERR_UNSUPPORTED),
+    (dict(decode_splits=-1), pe.PE_ERR_INVALID_ARG), (dict(decode_splits=257), pe.PE_ERR_INVALID_ARG),
+    (dict(decode_flat_order=2), pe.PE_ERR_INVALID_ARG), (dict(decode_shape=823), pe.PE_ERR_UNSUPPORTED),
+    (dict(decode_shape=424, head_dim=64), pe.PE_ERR_UNSUPPORTED),
+    (dict(decode_shape=432, layout=1), pe.PE_ERR_UNSUPPORTED)])
 def test_bad_descriptors(kw, want):
     d = _desc(**kw)
     L = pe.lib()
@@ -51,7 +55,7 @@ def test_bad_descriptors(kw, want):
     assert L.pe_evict_blocks(ctypes.byref(d), FAKE, FAKE, FAKE, 256, FAKE, FAKE, None) == want
     assert L.pe_paged_decode(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, ctypes.c_float(0.1), FAKE, FAKE, 1 << 30,
                              None) == want
-    assert pe.pe_workspace_bytes(pe.PE_OP_PAGED_DECODE, d) == 0
+    assert pe.pe_workspace_bytes(pe.PE_OP_PAGED_DECODE, d) == 0 and pe.pe_decode_splits(d) == 0
 
 
 def test_null_pointers_and_bad_budget():
@@ -71,6 +75,12 @@ def test_null_pointers_and_bad_budget():
                              1 << 30, None) == pe.PE_ERR_INVALID_ARG
     assert L.pe_prefill_prune(ctypes.byref(d), FAKE, FAKE, FAKE, 1000, 2000, 256, FAKE, FAKE, FAKE, FAKE, None, FAKE,
                               1 << 30, None) == pe.PE_ERR_INVALID_ARG   # max_seqlen > total_tokens
+    # the pruned row would not fit a table row: ceil(min(max_seqlen, C)/B) > max_blocks
+    small = _desc(max_blocks=8)
+    assert L.pe_prefill_prune(ctypes.byref(small), FAKE, FAKE, FAKE, 4000, 1000, 256, FAKE, FAKE, FAKE, FAKE, None,
+                              FAKE, 1 << 30, None) == pe.PE_ERR_INVALID_ARG
+    assert L.pe_prefill_prune(ctypes.byref(small), FAKE, FAKE, FAKE, 4000, 100, 256, FAKE, FAKE, FAKE, FAKE, None,
+                              None, 0, None) == pe.PE_ERR_WORKSPACE      # 7 pages fit: the next check is reached
     misaligned = ctypes.c_void_p(0x1004)
     assert L.pe_score_blocks(ctypes.byref(d), misaligned, FAKE, FAKE, FAKE, FAKE, None, 0, None) == pe.PE_ERR_INVALID_ARG
 
@@ -93,19 +103,18 @@ def test_workspace_checks():
     assert L.pe_prefill_prune(*args, None, 0, None) == pe.PE_ERR_WORKSPACE
     assert L.pe_prefill_prune(*args, FAKE, need - 1, None) == pe.PE_ERR_WORKSPACE
     assert L.pe_prefill_prune(*args, ctypes.c_void_p(0x1010), need, None) == pe.PE_ERR_WORKSPACE   # misaligned
-    # decode: the split count (and with it the workspace) follows the option
-    pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, 1)
-    try:
-        assert pe.pe_workspace_bytes(pe.PE_OP_PAGED_DECODE, d) == 0
-        pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, 4)
-        w4 = pe.pe_workspace_bytes(pe.PE_OP_PAGED_DECODE, d)
-        assert w4 == 4 * 32 * 4 * (128 + 2) * 4
-        assert L.pe_paged_decode(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, FAKE, ctypes.c_float(0.1), FAKE, FAKE,
-                                 w4 - 1, None) == pe.PE_ERR_WORKSPACE
-    finally:
-        pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, 0)
-    with pytest.raises(pe.PeError):
-        pe.pe_set_option(99, 1)
+    # decode: the split count (and with it the workspace) follows the descriptor
+    d1 = _desc(decode_splits=1)
+    assert pe.pe_decode_splits(d1) == 1 and pe.pe_workspace_bytes(pe.PE_OP_PAGED_DECODE, d1) == 0
+    d4 = _desc(decode_splits=4)
+    w4 = pe.pe_workspace_bytes(pe.PE_OP_PAGED_DECODE, d4)
+    assert pe.pe_decode_splits(d4) == 4 and w4 == 4 * 32 * 4 * (128 + 2) * 4
+    assert L.pe_paged_decode(ctypes.byref(d4), FAKE, FAKE, FAKE, FAKE, FAKE, ctypes.c_float(0.1), FAKE, FAKE,
+                             w4 - 1, None) == pe.PE_ERR_WORKSPACE
+    # two descriptors in one process do not interfere, and the automatic choice covers the compute units
+    assert pe.pe_decode_splits(d1) == 1 and pe.pe_decode_splits(d) >= 1
+    assert pe.pe_workspace_bytes(pe.PE_OP_PAGED_DECODE, d) == pe.pe_decode_splits(d) * 4 * 32 * (128 + 2) * 4 * (
+        pe.pe_decode_splits(d) > 1)
     assert pe.pe_workspace_bytes(pe.PE_OP_SCORE_BLOCKS, d) == 0 and pe.pe_workspace_bytes(pe.PE_OP_EVICT_BLOCKS, d) == 0
 
 

@@ -10,7 +10,7 @@ import oracle
 from oracle.decode_loop import decode_step as oracle_step
 from paper_2509_04377_amd import binding as pe
 from paper_2509_04377_amd import synth
-from paper_2509_04377_amd.engine import LayeredCache
+from paper_2509_04377_amd.engine import LayeredCache, PagedCache
 
 from _util import f32, i32, oracle_prefill, rel_err
 
@@ -39,7 +39,7 @@ def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=Fals
     ocache, okept, _ = oracle_prefill(wl, lens, k_in, v_in, cu, layout, wl.budget)
 
     S, Hk, Hq, D, B = wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim, wl.block_size
-    gcache = pe.PagedCache.create(wl.torch_dtype, S, Hk, Hq, D, B, layout, wl.budget, DEV)
+    gcache = PagedCache.create(wl.torch_dtype, S, Hk, Hq, D, B, layout, wl.budget, DEV)
     kept = torch.full((S, Hk, wl.budget), -9, dtype=torch.int32, device=DEV)
     gcache.prefill_prune(k_in.to(DEV), v_in.to(DEV), cu.to(DEV), max(lens), kept)
     gcache.set_host_lens(lens)

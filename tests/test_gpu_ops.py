@@ -236,6 +236,45 @@ def test_evict_blocks_bit_exact():
     assert (ev >= 0).any() and (ev < 0).any()
 
 
+def test_evict_blocks_nan_scores_stay_inside_the_row():
+    """Scores that are all NaN (finite K/V never produce one) must not send the compaction outside the table row:
+    the first candidate page goes.  A NaN among real scores never wins."""
+    print("case evict_blocks_nan", flush=True)
+    B, Hk, S, mb = 16, 3, 4, 70
+    n_pages = [5, 66, 8, 12]
+    lens = np.array([n * B for n in n_pages], np.int32)
+    rng = np.random.default_rng(310)
+    table = np.full((S, Hk, mb), -1, np.int32)
+    for s in range(S):
+        for h in range(Hk):
+            table[s, h, :n_pages[s]] = rng.permutation(1000)[:n_pages[s]] + 1000 * (s * Hk + h)
+    scores = np.full((S, Hk, mb), np.nan, np.float32)
+    scores[2, 1, :8] = [3, np.nan, 2, 2, np.nan, 5, 9, 4]       # a NaN among real scores: first minimum is page 2
+    desc = pe.make_desc(torch.float32, S, Hk, Hk, 64, B, mb, 1000 * S * Hk)
+    for opts, lo in ((None, 0), (dict(protect_first=3), 3), (dict(share_heads=1), 0),
+                     (dict(share_heads=1, protect_first=2, protect_last=1), 2)):
+        t_gpu, l_gpu = torch.tensor(table, device=DEV), torch.tensor(lens, device=DEV)
+        ev_gpu = torch.full((S, Hk), -7, dtype=torch.int32, device=DEV)
+        fr_gpu = torch.full((S, Hk), -7, dtype=torch.int32, device=DEV)
+        if opts is None:
+            pe.pe_evict_blocks(desc, torch.tensor(scores, device=DEV), t_gpu, l_gpu, 2 * B, ev_gpu, fr_gpu)
+        else:
+            o = pe.pe_evict_opts(0, opts.get("protect_first", 0), opts.get("protect_last", 0), opts.get("share_heads", 0), 0)
+            pe.pe_evict_blocks_ex(desc, o, torch.tensor(scores, device=DEV), t_gpu, l_gpu, 2 * B, ev_gpu, fr_gpu)
+        torch.cuda.synchronize()
+        ev, fr, t_new = ev_gpu.cpu().numpy(), fr_gpu.cpu().numpy(), t_gpu.cpu().numpy()
+        for s in range(S):
+            for h in range(Hk):
+                want = lo
+                if opts is None and (s, h) == (2, 1):
+                    want = 2
+                assert ev[s, h] == want, (opts, s, h, ev[s, h])
+                assert fr[s, h] == table[s, h, want]
+                assert np.array_equal(t_new[s, h, :n_pages[s] - 1], np.delete(table[s, h, :n_pages[s]], want))
+                assert np.all(t_new[s, h, n_pages[s] - 1:] == -1)
+        assert np.array_equal(l_gpu.cpu().numpy(), lens - B)
+
+
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("D,B", [(64, 16), (128, 16), (64, 32), (128, 32), (128, 64), (64, 128)])
 @pytest.mark.parametrize("G", [1, 2, 3, 4, 6, 8])
@@ -253,7 +292,7 @@ def test_paged_decode_shapes(dt, D, B, G):
     kd, vd, td, ld, qd = (x.to(DEV) for x in (k_pool, v_pool, table, sl, q))
     try:
         for splits in (0, 1, 3, 8):
-            pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, splits)
+            desc.decode_splits = splits
             ws = pe.alloc_workspace(pe.PE_OP_PAGED_DECODE, desc)
             out = torch.full((S, Hq, D), 7.0, dtype=DTYPES[dt], device=DEV)
             pe.pe_paged_decode(desc, qd, kd, vd, td, ld, D ** -0.5, out, ws)
@@ -263,7 +302,7 @@ def test_paged_decode_shapes(dt, D, B, G):
             e2, emax = rel_err(got[1:], want[1:])
             assert e2 <= TOL[dt] and emax <= TOL[dt], (splits, e2, emax)
     finally:
-        pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, 0)
+        desc.decode_splits = 0
 
 
 def test_paged_decode_masks_junk_and_extreme_logits():
@@ -411,7 +450,7 @@ def test_append_paged_decode_fused(dt, D, B, G):
     g = torch.Generator().manual_seed(801)
     try:
         for step, splits in enumerate((1, 3, 0)):
-            pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, splits)
+            desc.decode_splits = splits
             ws = pe.alloc_workspace(pe.PE_OP_APPEND_PAGED_DECODE, desc)
             nk = torch.randn((S, Hk, D), generator=g).to(DTYPES[dt])
             nv = torch.randn((S, Hk, D), generator=g).to(DTYPES[dt])
@@ -432,7 +471,7 @@ def test_append_paged_decode_fused(dt, D, B, G):
                 e2, emax = rel_err(f32(out), want)
                 assert e2 <= TOL[dt] and emax <= TOL[dt], (step, rep, e2, emax)
     finally:
-        pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, 0)
+        desc.decode_splits = 0
 
 
 @pytest.mark.parametrize("opts", [dict(policy=0, protect_first=2, protect_last=3), dict(policy=1, protect_first=4),

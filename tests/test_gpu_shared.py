@@ -7,6 +7,7 @@ import torch
 from oracle import shared as osh
 from paper_2509_04377_amd import binding as pe
 from paper_2509_04377_amd import synth
+from paper_2509_04377_amd.engine import PagedCache
 
 from _util import f32, i32, rel_err
 
@@ -120,7 +121,7 @@ def test_shared_paged_decode(dt, D, B, Hk, G):
     kd, vd, td, ld, qd = (x.to(DEV) for x in (k, v, table, sl, q))
     try:
         for splits in (0, 1, 3, 8):
-            pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, splits)
+            desc.decode_splits = splits
             ws = pe.alloc_workspace(pe.PE_OP_PAGED_DECODE, desc)
             out = torch.full((S, Hq, D), 7.0, dtype=DTYPES[dt], device=DEV)
             pe.pe_paged_decode(desc, qd, kd, vd, td, ld, D ** -0.5, out, ws)
@@ -130,7 +131,7 @@ def test_shared_paged_decode(dt, D, B, Hk, G):
             e2, emax = rel_err(got[1:], want[1:])
             assert e2 <= TOL[dt] and emax <= TOL[dt], (splits, e2, emax)
     finally:
-        pe.pe_set_option(pe.PE_OPT_DECODE_SPLITS, 0)
+        desc.decode_splits = 0
 
 
 @pytest.mark.parametrize("dt,D,B,Hk", [("bf16", 128, 16, 8), ("f32", 64, 32, 3), ("f32", 128, 16, 8)])
@@ -227,7 +228,7 @@ def run_shared_loop(wl, steps, layer=0, cached_scores=False, policy=0, protect_f
     o_lens, o_kept = osh.prefill_prune(f32(k_in), f32(v_in), i32(cu), wl.budget, kp, vp, table)
     oc = osh.SharedOracleCache(kp, vp, table, o_lens, i32(layout.spare[:, 0]).copy(), np.zeros(S, np.int32),
                                np.full(S, -1, np.int32), wl.budget)
-    gc = pe.PagedCache.create(wl.torch_dtype, S, Hk, Hq, D, B, layout, wl.budget, DEV, shared=True)
+    gc = PagedCache.create(wl.torch_dtype, S, Hk, Hq, D, B, layout, wl.budget, DEV, shared=True)
     kept = torch.full((S, wl.budget), -9, dtype=torch.int32, device=DEV)
     gc.prefill_prune(k_in.to(DEV), v_in.to(DEV), cu.to(DEV), max(lens), kept)
     gc.set_host_lens(lens)
