@@ -250,6 +250,23 @@ int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * (4) for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as pe_paged_decode, but
+ * the split partials live in a static device array inside the library (PE_STATIC_SCRATCH_BYTES per GPU, held
+ * until the process ends) instead of a caller workspace.  The call allocates and frees nothing.  A shape whose
+ * partials, pe_workspace_bytes(PE_OP_PAGED_DECODE, desc, 0), exceed PE_STATIC_SCRATCH_BYTES is refused with
+ * PE_ERR_WORKSPACE and nothing is launched (lower desc->decode_splits, or use pe_paged_decode).  The first call
+ * on a device looks the array's address up once (hipGetSymbolAddress; make that call outside stream capture).
+ * All calls on one GPU share the one array: calls that overlap in time on the same GPU (different streams) race;
+ * order them on one stream.  Nothing needs clearing between calls: every record the merge reads is written by
+ * the same call's attention kernel.
+ */
+#define PE_STATIC_SCRATCH_BYTES (8 * 1024 * 1024)
+int pe_paged_decode_static(const pe_cache_desc* desc, const void* q, const void* k_pool, const void* v_pool,
+                           const int32_t* block_table, const int32_t* seq_lens, float softmax_scale, void* out,
+                           void* stream);
+
+/*
  * Harness convenience (not part of the paper's method): the step between (3) and (4) in a decode
  * iteration.  Writes the new token's K/V row of every (s, hk) into slot seq_lens[s] % B of the tail
  * page.  When seq_lens[s] % B == 0 a new page is linked in at logical index seq_lens[s]/B: the page

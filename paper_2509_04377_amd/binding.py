@@ -18,11 +18,12 @@ PE_ERR_INVALID_ARG, PE_ERR_UNSUPPORTED, PE_ERR_WORKSPACE, PE_ERR_HIP = -1, -2, -
 PE_F32, PE_BF16 = 0, 1
 PE_OP_SCORE_BLOCKS, PE_OP_PREFILL_PRUNE, PE_OP_EVICT_BLOCKS, PE_OP_PAGED_DECODE = 0, 1, 2, 3
 PE_OP_APPEND_PAGED_DECODE = 4
+PE_STATIC_SCRATCH_BYTES = 8 * 1024 * 1024
 
 EXPORTS = ["pe_workspace_bytes", "pe_status_string", "pe_version", "pe_decode_splits",
            "pe_score_blocks", "pe_prefill_prune", "pe_evict_blocks", "pe_paged_decode", "pe_append_kv",
            "pe_append_paged_decode", "pe_score_recent_blocks", "pe_evict_blocks_cached", "pe_evict_blocks_ex", "pe_score_evict",
-           "pe_score_triggered_blocks"]
+           "pe_score_triggered_blocks", "pe_paged_decode_static"]
 
 
 class pe_cache_desc(ctypes.Structure):
@@ -81,6 +82,8 @@ def lib():
         L.pe_score_evict.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.pe_paged_decode.restype = ctypes.c_int
         L.pe_paged_decode.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+        L.pe_paged_decode_static.restype = ctypes.c_int
+        L.pe_paged_decode_static.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp]
         L.pe_append_kv.restype = ctypes.c_int
         L.pe_append_kv.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.pe_append_paged_decode.restype = ctypes.c_int
@@ -267,6 +270,15 @@ def pe_paged_decode(desc, q, k_pool, v_pool, block_table, seq_lens, softmax_scal
     check(lib().pe_paged_decode(ctypes.byref(desc), ptr(q, "q"), ptr(k_pool, "k_pool"), ptr(v_pool, "v_pool"),
                                  ptr(block_table, "block_table", torch.int32), ptr(seq_lens, "seq_lens", torch.int32),
                                  ctypes.c_float(softmax_scale), ptr(out, "out"), wp, wn, stream_arg()), "pe_paged_decode")
+
+
+def pe_paged_decode_static(desc, q, k_pool, v_pool, block_table, seq_lens, softmax_scale, out):
+    if HostOnly.active:
+        return
+    check(lib().pe_paged_decode_static(ctypes.byref(desc), ptr(q, "q"), ptr(k_pool, "k_pool"), ptr(v_pool, "v_pool"),
+                                       ptr(block_table, "block_table", torch.int32),
+                                       ptr(seq_lens, "seq_lens", torch.int32), ctypes.c_float(softmax_scale),
+                                       ptr(out, "out"), stream_arg()), "pe_paged_decode_static")
 
 
 def pe_append_kv(desc, new_k, new_v, k_pool, v_pool, block_table, seq_lens, freed_phys, spare, spare_used):

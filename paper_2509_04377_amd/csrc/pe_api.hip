@@ -3,8 +3,13 @@
 #include "../../include/pe.h"
 
 #include <atomic>
+#include <mutex>
 
 #include "pe_launch.h"
+
+// Split partials of pe_paged_decode_static: one copy per GPU, held until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
+static __device__ __align__(256) unsigned char scratch[PE_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -347,6 +352,57 @@ int pe_paged_decode(const pe_cache_desc* desc, const void* q, const void* k_pool
   a.seq_lens = seq_lens;
   a.out = out;
   a.partials = static_cast<float*>(workspace);
+  a.scale = softmax_scale;
+  return pe::launch_paged_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
+}
+
+namespace {
+// Device address of `scratch` on the current device, looked up once per device (every GPU holds its own copy of
+// the array at its own address).
+int static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return PE_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return PE_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return PE_ERR_HIP;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return PE_OK;
+}
+}  // namespace
+
+int pe_paged_decode_static(const pe_cache_desc* desc, const void* q, const void* k_pool, const void* v_pool,
+                           const int32_t* block_table, const int32_t* seq_lens, float softmax_scale, void* out,
+                           void* stream) {
+  const int st = check_desc(desc);
+  if (st != PE_OK) return st;
+  if (!q || !k_pool || !v_pool || !block_table || !seq_lens || !out) return PE_ERR_INVALID_ARG;
+  if (!aligned(k_pool, 16) || !aligned(v_pool, 16) || !aligned(q, 16)) return PE_ERR_INVALID_ARG;
+  if (!finite(softmax_scale)) return PE_ERR_INVALID_ARG;
+  const int splits = decode_splits(desc);
+  const size_t need = pe::decode_partials_bytes(desc->num_seqs, desc->num_q_heads, desc->head_dim, splits);
+  if (need > (size_t)PE_STATIC_SCRATCH_BYTES) return PE_ERR_WORKSPACE;  // the partials would not fit the array
+  void* partials = nullptr;
+  if (need > 0) {
+    const int sc = static_scratch(&partials);
+    if (sc != PE_OK) return sc;
+  }
+  pe::DecodeArgs a = decode_args(desc, splits);
+  a.q = q;
+  a.k_pool = k_pool;
+  a.v_pool = v_pool;
+  a.block_table = block_table;
+  a.seq_lens = seq_lens;
+  a.out = out;
+  // every (row, split, head) record the merge reads is written by the attention kernel of the same call (empty
+  // splits write (acc, m, l) = (0, -inf, 0)), so what an earlier call left in the array never shows
+  a.partials = static_cast<float*>(partials);
   a.scale = softmax_scale;
   return pe::launch_paged_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }

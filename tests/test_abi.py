@@ -118,6 +118,16 @@ def test_workspace_checks():
     assert pe.pe_workspace_bytes(pe.PE_OP_SCORE_BLOCKS, d) == 0 and pe.pe_workspace_bytes(pe.PE_OP_EVICT_BLOCKS, d) == 0
 
 
+def test_static_scratch_rejects_oversized_partials():
+    """pe_paged_decode_static refuses a shape whose split partials exceed its static array (host check)."""
+    S, Hk, Hq, D = 64, 8, 64, 128
+    desc = pe.make_desc(pe.PE_BF16, S, Hk, Hq, D, 16, 64, 4096, decode_splits=64)
+    assert pe.pe_workspace_bytes(pe.PE_OP_PAGED_DECODE, desc) > pe.PE_STATIC_SCRATCH_BYTES
+    fake = ctypes.c_void_p(0x1000)
+    rc = pe.lib().pe_paged_decode_static(ctypes.byref(desc), fake, fake, fake, fake, fake, ctypes.c_float(0.1), fake, None)
+    assert rc == pe.PE_ERR_WORKSPACE
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(pe, "_lib", None)
     monkeypatch.setattr(pe, "LIB_PATH", "/nonexistent/libpe.so")
