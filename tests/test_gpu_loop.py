@@ -7,6 +7,7 @@ import pytest
 import torch
 
 import oracle
+from oracle import shared as osh
 from oracle.decode_loop import decode_step as oracle_step
 from paper_2509_04377_amd import binding as pe
 from paper_2509_04377_amd import synth
@@ -304,6 +305,24 @@ def test_full_size_one_layer_and_determinism(wl):
     assert e2 <= 2e-2 and emax <= 2e-2
 
 
+def _oracle_layer_state(wl, lens, k_in, v_in, cu, layout, l, shared):
+    """Oracle cache of layer `l` of a layered run: the oracle's own prune of that layer's prompts into pools of
+    the shared size, with the layer's slice of the table and of the spare lists."""
+    S, Hk, D, B, C = wl.num_seqs, wl.num_kv_heads, wl.head_dim, wl.block_size, wl.budget
+    rows = slice(l * S, (l + 1) * S)
+    if not shared:
+        lay = synth.PageLayout(layout.block_table[rows], layout.spare[rows], layout.max_blocks, layout.n_spare,
+                               layout.num_phys_blocks)
+        return oracle_prefill(wl, lens, k_in, v_in, cu, lay, C)[0]
+    P = layout.num_phys_blocks
+    kp = np.zeros((P, B, Hk, D), np.float32)
+    vp = np.zeros_like(kp)
+    table = i32(layout.block_table[rows, 0]).copy()
+    o_lens, _ = osh.prefill_prune(f32(k_in), f32(v_in), i32(cu), C, kp, vp, table)
+    return osh.SharedOracleCache(kp, vp, table, o_lens, i32(layout.spare[rows, 0]).copy(), np.zeros(S, np.int32),
+                                 np.full(S, -1, np.int32), C)
+
+
 @pytest.mark.parametrize("shared,stagger", [(False, False), (False, True), (True, False), (True, True)])
 def test_all_driver_modes_agree_at_full_size(shared, stagger):
     """The whole headline job (32 layers x 32 sequences x 8 KV heads at budget 2048, one shared shuffled pool)
@@ -312,7 +331,9 @@ def test_all_driver_modes_agree_at_full_size(shared, stagger):
     lengths and spare counters, bit for bit (the decisions are the same decisions), and the same attention
     outputs within the bf16 tolerance (the fused and the separate attention sum in different orders).  Also in
     the head-shared layout (which has no one-launch score+evict), and with prompts just under the budget so that
-    the sequences evict at different steps."""
+    the sequences evict at different steps.  In the first mode one layer of the 32 is stepped by the oracle as
+    well: its table, lengths, spare counters and attention outputs are compared at every step, so the other
+    modes are compared with a run that is itself checked against the oracle."""
     from paper_2509_04377_amd.engine import GraphedStepper
     print("case loop modes agree", shared, stagger, flush=True)
     wl = synth.LLAMA31_8B
@@ -326,14 +347,18 @@ def test_all_driver_modes_agree_at_full_size(shared, stagger):
     nv = torch.randn((4, L, S, Hk, D), generator=g, device=DEV).to(wl.torch_dtype)
     q = torch.randn((4, L, S, Hq, D), generator=g, device=DEV).to(wl.torch_dtype)
     ref = None
+    ls = 17          # the layer of the first mode's run that is stepped by the oracle as well
     for mode in ("paper", "cached", "fused_evict", "unfused", "graph"):
         if shared and mode == "fused_evict":
             continue
         layout = synth.page_layout(wl, lens * L, SEED, steps=steps, shared=shared)
         eng = LayeredCache(wl.torch_dtype, L, S, Hk, Hq, D, B, layout, C, DEV, shared=shared)
+        ocache = None
         for l in range(L):
             k_in, v_in, _ = synth.prompt_kv(wl, l, lens, SEED, device=DEV)
             eng.prefill_prune_layer(l, k_in, v_in, cu, max(lens))
+            if mode == "paper" and l == ls:
+                ocache = _oracle_layer_state(wl, lens, k_in, v_in, cu, layout, l, shared)
             del k_in, v_in
         eng.set_host_lens(lens)
         eng.folded.cached_scores = mode == "cached"
@@ -351,6 +376,16 @@ def test_all_driver_modes_agree_at_full_size(shared, stagger):
                 n_trig += bool(stepper.step())
             else:
                 n_trig += bool(eng.decode_step(nk[i], nv[i], q[i], out))
+            if ocache is not None:      # the sampled layer against the oracle, every step
+                ostep = osh.decode_step if shared else oracle_step
+                want = ostep(ocache, f32(nk[i][ls]), f32(nv[i][ls]), f32(q[i][ls]))[0]
+                gl = eng.per_layer[ls]
+                where = "layer %d step %d" % (ls, st)
+                assert np.array_equal(gl.block_table.cpu().numpy(), ocache.block_table), where
+                assert np.array_equal(gl.seq_lens.cpu().numpy(), ocache.seq_lens), where
+                assert np.array_equal(gl.spare_used.cpu().numpy(), ocache.spare_used), where
+                e2, emax = rel_err(f32(out[ls]), want)
+                assert e2 <= 2e-2 and emax <= 2e-2, (where, e2, emax)
         torch.cuda.synchronize()
         assert n_trig == (steps if stagger else 3)
         state = (eng.folded.block_table.clone(), eng.folded.seq_lens.clone(), eng.folded.spare_used.clone(),
