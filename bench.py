@@ -9,6 +9,10 @@ folded into the sequence dimension), then per layer the append of the new token 
 back to back on one stream.  K/V pools, tables and the per-step inputs are resident in HBM before the
 timed region.  Prints ONE JSON line: tokens/s of the whole job, the roofline object of the attention kernel
 (algorithmic bytes per launch over its measured launch time, against 8 TB/s) and the CPU oracle's rate.
+The headline workload is timed first; after it every other benchmark configuration (tiny, the 1B shape at its
+three budgets, the 3B shape, both long-context corners) is run for a short, whole number of trigger periods and
+reported under "configs" in the same line, each with its own attention roofline and its prefill-prune time
+(device events).  `--no-configs` skips them.
 """
 import argparse
 import json
@@ -33,6 +37,7 @@ def parse_args():
     ap.add_argument("--workload", default="llama31_8b")
     ap.add_argument("--budget", type=int, default=None)
     ap.add_argument("--block-size", type=int, default=None, help="override the page size (16, 32, 64, 128)")
+    ap.add_argument("--context", type=int, default=None, help="override the prompt length (one value for all sequences)")
     ap.add_argument("--q-heads", type=int, default=None, help="override the number of query heads (group size probe)")
     ap.add_argument("--seed", type=int, default=2509)
     ap.add_argument("--splits", type=int, default=None, help="override the split count of pe_paged_decode")
@@ -55,27 +60,48 @@ def parse_args():
                          "boundaries at different steps, as in a serving batch (the prefill prune is then a plain copy)")
     ap.add_argument("--graph", action="store_true", help="replay each step from captured HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true", help="skip the short runs of the other configurations")
     ap.add_argument("--no-kernel-breakdown", action="store_true")
-    ap.add_argument("--cpu-seqs", type=int, default=16)
-    ap.add_argument("--cpu-layers", type=int, default=2)
-    ap.add_argument("--cpu-steps", type=int, default=33)
+    ap.add_argument("--cpu-seqs", type=int, default=32)
+    ap.add_argument("--cpu-layers", type=int, default=4)
+    ap.add_argument("--cpu-steps", type=int, default=97)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference dispatch for rocprofv3 --pmc scaling)")
     return ap.parse_args()
 
 
+def kernel_source_hash():
+    """sha256 over the sources that make up the attention kernel; a committed counter summary names the hash of
+    the sources it was measured on, and is only quoted while they are unchanged."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("paged_decode.hip", "pe_device.h", "pe_launch.h"):
+        with open(os.path.join(ROOT, "paper_2509_04377_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def traffic_from_profiles(workload):
-    """HBM bytes per attention launch measured with rocprofv3 --pmc, if a summary is committed."""
+    """HBM bytes per attention launch from the committed rocprofv3 --pmc summary of this workload, with where it
+    came from.  Not measured in this run: (None, reason) when there is no summary or it was taken on other
+    kernel sources."""
     if workload is None:
-        return None
-    path = os.path.join(ROOT, "profiles", "paged_decode_%s_pmc.md" % workload)
+        return None, "no counter summary for an overridden workload"
+    rel = os.path.join("profiles", "paged_decode_%s_pmc.md" % workload)
+    val, src_hash = None, None
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+                val = float(line.split(":")[1])
+            if line.startswith("kernel_source_sha256:"):
+                src_hash = line.split(":")[1].strip()
     except OSError:
-        pass
-    return None
+        return None, "no committed counter summary"
+    if val is None:
+        return None, "no committed counter summary"
+    if src_hash != kernel_source_hash():
+        return None, "%s was measured on other kernel sources (%s, now %s)" % (rel, src_hash, kernel_source_hash())
+    return val, "committed rocprofv3 --pmc summary %s (FETCH_SIZE + WRITE_SIZE, copy-calibrated), not this run" % rel
 
 
 def build_engine(wl, seed, dev, shared=False, stagger=False, decode_opts=None):
@@ -92,18 +118,28 @@ def build_engine(wl, seed, dev, shared=False, stagger=False, decode_opts=None):
                        wl.block_size, layout, wl.budget, dev, shared=shared, decode_opts=decode_opts)
     total = sum(lens)
     ws = pe.alloc_workspace(pe.PE_OP_PREFILL_PRUNE, eng.per_layer[0].desc, total, device=dev)
-    prune_ms = []
+    # one warm-up prune of layer 0 (it is pruned again below), then every layer between two events
+    k_in, v_in, cu = synth.prompt_kv(wl, 0, lens, seed, device=dev)
+    eng.prefill_prune_layer(0, k_in, v_in, cu, max(lens), None, ws)
+    marks = []
     for l in range(wl.layers):
         k_in, v_in, cu = synth.prompt_kv(wl, l, lens, seed, device=dev)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
         eng.prefill_prune_layer(l, k_in, v_in, cu, max(lens), None, ws)
-        torch.cuda.synchronize()
-        prune_ms.append((time.perf_counter() - t0) * 1e3)
+        e1.record()
+        marks.append((e0, e1))
         del k_in, v_in
+    torch.cuda.synchronize()
+    prune_ms = sorted(a.elapsed_time(b) for a, b in marks)
     eng.set_host_lens(lens)
     elem = 2 if wl.dtype == "bf16" else 4
-    prune_bytes = 2 * total * wl.num_kv_heads * wl.head_dim * elem      # K and V sweep of one layer
+    row_bytes = wl.num_kv_heads * wl.head_dim * elem
+    kept = sum(min(n, wl.budget) for n in lens)
+    # per layer: the K and V sweep of the whole prompt, the gather's reads of the kept rows and its writes
+    prune_bytes = {"sweep": 2 * total * row_bytes, "gather_read": 2 * kept * row_bytes,
+                   "gather_write": 2 * kept * row_bytes}
     return eng, lens, prune_ms, prune_bytes
 
 
@@ -207,39 +243,20 @@ def kernel_breakdown(eng, wl, new_k, new_v, q, out):
                              "frac_of_hbm_peak": att_bytes / med(att) / 1e3 / HBM_PEAK_GBS}}
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (rows are independent, the path shards with no collective); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
+def workload_label(wl):
+    return ("%s: %d layers, %d seqs x %d KV heads (%d q heads), head_dim %d, page %d, context %s -> budget %d"
+            % (wl.name, wl.layers, wl.num_seqs, wl.num_kv_heads, wl.num_q_heads, wl.head_dim, wl.block_size,
+               "/".join(map(str, wl.context)), wl.budget))
+
+
+def run_workload(wl, args, dev, steps, warmup, shared=False, stagger=False, decode_opts=None, sample_every=8,
+                 breakdown=False, profile_key=None):
+    """Prune all layers (device-event timed), then `warmup` untimed and exactly `steps` timed decode steps.
+    Returns the measurements of this workload as a dict."""
     import torch
     from paper_2509_04377_amd import binding as pe
-    from paper_2509_04377_amd import synth
 
-    wl = synth.WORKLOADS[args.workload]
-    if args.budget is not None:
-        wl = wl.with_(budget=args.budget)
-    if args.block_size is not None:
-        wl = wl.with_(block_size=args.block_size)
-    if args.q_heads is not None:
-        wl = wl.with_(num_q_heads=args.q_heads)
-    dev = "cuda:0"
-    torch.cuda.set_device(0)
-    decode_opts = {}
-    if args.splits is not None:
-        decode_opts["decode_splits"] = args.splits
-    if args.xcd_map is not None:
-        decode_opts["decode_flat_order"] = 1 - args.xcd_map
-    if args.waves is not None or args.depth is not None or args.loads is not None:
-        decode_opts["decode_shape"] = (args.waves or 4) * 100 + (args.depth or 2) * 10 + (args.loads or 2)
-
-    shared = args.layout == "shared"
-    # the committed counter summary covers the workload as defined, in the per-head layout; any override of the
-    # shape changes the bytes, so no measured traffic is quoted then
-    overridden = any(v is not None for v in (args.budget, args.block_size, args.q_heads)) or args.stagger
-    profile_key = None if overridden else wl.name + ("_shared" if shared else "")
-    eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev, shared, args.stagger, decode_opts)
+    eng, lens, prune_ms, prune_bytes = build_engine(wl, args.seed, dev, shared, stagger, decode_opts)
     # shared layout: the combined call is two launches inside the library; issue them separately here so that the
     # events bracket the attention kernel alone
     eng.fused = not args.unfused and not shared
@@ -263,17 +280,18 @@ def main():
     if args.graph:      # fixed input buffers, as a serving loop keeps them; warm-up also captures the graphs
         from paper_2509_04377_amd.engine import GraphedStepper
         stepper = GraphedStepper(eng, new_k[0], new_v[0], q[0], out)
-    for st in range(args.warmup):
+    for st in range(warmup):
         if stepper is not None:
             stepper.step()
         else:
             eng.decode_step(new_k[st % ring], new_v[st % ring], q[st % ring], out)
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly --steps steps ---------------------------------------------------------
+    # ---- timed region: exactly `steps` steps -----------------------------------------------------------
     # (event_start, event_end, launches between them, algorithmic bytes of those launches).  With the fused
     # append the attention launches of a step run back to back, so one event pair brackets all of them and
     # the event overhead is not charged to each launch; unfused, every attention launch gets its own pair.
+    # A launch is the whole attention call: on split rows the partial kernel and the merge kernel together.
     samples = []
     state = {}
 
@@ -295,15 +313,15 @@ def main():
             e.record()
             samples.append((state["e0"], e, 1, per_launch))
 
-    sample_every = min(args.sample_every, args.steps)   # a short run still times the launches of one step
-    step_events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    sample_every = min(sample_every, steps)   # a short run still times the launches of one step
+    step_events = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     n_trigger = 0        # steps on which some sequence evicts
     n_trigger_seqs = 0   # sequence-evictions over the timed region (each scores its own pages)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     step_events[0].record()
-    for st in range(args.steps):
-        i = (args.warmup + st) % ring
+    for st in range(steps):
+        i = (warmup + st) % ring
         sampled = sample_every > 0 and st % sample_every == sample_every // 2
         n_trigger_seqs += sum(eng._triggers())
         if stepper is not None:
@@ -320,48 +338,126 @@ def main():
     elapsed = time.perf_counter() - t0
     # ---------------------------------------------------------------------------------------------------
 
-    step_ms = sorted(step_events[i].elapsed_time(step_events[i + 1]) for i in range(args.steps))
-    tokens_per_s = S * args.steps / elapsed
-    result = {
-        "metric": "decode tokens/s (score+evict+paged attn), %s shape" % SHAPE_NAMES.get(wl.name, wl.name),
-        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": "%s: %d layers, %d seqs x %d KV heads (%d q heads), head_dim %d, page %d, context %s -> "
-                               "budget %d" % (wl.name, L, S, Hk, Hq, D, wl.block_size, "/".join(map(str, wl.context)),
-                                              wl.budget),
-                   "layout": args.layout, "stagger": args.stagger, "decode_splits": pe.pe_decode_splits(eng.per_layer[0].desc), "fused_append": eng.fused, "cached_scores": args.cached_scores, "fused_evict": args.fused_evict, "hip_graph": args.graph,
-                   "trigger_steps": n_trigger, "sequence_evictions": n_trigger_seqs},
+    step_ms = sorted(step_events[i].elapsed_time(step_events[i + 1]) for i in range(steps))
+    prune_med = prune_ms[len(prune_ms) // 2]
+    moved = sum(prune_bytes.values())
+    r = {
+        "tokens_per_s": S * steps / elapsed, "ms_per_step": elapsed / steps * 1e3, "steps": steps, "warmup": warmup,
         "step_ms": {"p50": step_ms[len(step_ms) // 2], "p99": step_ms[min(len(step_ms) - 1, int(len(step_ms) * 0.99))],
                     "max": step_ms[-1]},
-        # host-timed per layer (four launches and a synchronisation), against the K/V bytes the sweep reads
-        "prefill_prune": {"ms_per_layer": sorted(prune_ms)[len(prune_ms) // 2],
-                          "sweep_GBps": prune_bytes / (sorted(prune_ms)[len(prune_ms) // 2] * 1e-3) / 1e9,
-                          "sweep_frac_of_hbm_peak": prune_bytes / (sorted(prune_ms)[len(prune_ms) // 2] * 1e-3) / 1e9
-                          / HBM_PEAK_GBS},
+        "decode_splits": pe.pe_decode_splits(eng.per_layer[0].desc), "fused_append": eng.fused,
+        "trigger_steps": n_trigger, "sequence_evictions": n_trigger_seqs,
+        # device events around the four launches of each layer's prune; bytes: the K/V sweep of the whole prompt
+        # plus the gather's reads and writes of the kept rows
+        "prefill_prune": {"ms_per_layer": prune_med, "timing": "HIP events, median over layers",
+                          "bytes_per_layer": prune_bytes, "GBps": moved / (prune_med * 1e-3) / 1e9,
+                          "frac_of_hbm_peak": moved / (prune_med * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                          "sweep_GBps": prune_bytes["sweep"] / (prune_med * 1e-3) / 1e9},
+        "roofline": None,   # stays None when no step could be sampled (graph replay of trigger-only runs)
+        "path_GBps": None,
     }
-    result["roofline"] = None   # stays None when no step could be sampled (graph replay of trigger-only runs)
     if samples:
         n_launch = sum(n for _, _, n, _ in samples)
         avg_dur = sum(a.elapsed_time(b) * 1e-3 for a, b, _, _ in samples) / n_launch
         avg_bytes = sum(nb for _, _, _, nb in samples) / n_launch
         achieved = avg_bytes / avg_dur / 1e9
-        result["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(profile_key),
-                              "kernel": "paged_decode_kernel", "launches_timed": n_launch,
-                              "avg_launch_us": avg_dur * 1e6, "algorithmic_bytes_per_launch": avg_bytes}
-    # whole-step algorithmic bytes: attention every step + the score sweep on trigger steps
-    result["path_GBps"] = None
-    if samples:
-        mean_cached = avg_bytes                                              # per layer launch
+        traffic, traffic_source = traffic_from_profiles(profile_key)
+        r["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                         "kernel": "paged_decode_kernel" + (" + paged_decode_reduce_kernel" if r["decode_splits"] > 1
+                                                            else ""),
+                         "launches_timed": n_launch, "avg_launch_us": avg_dur * 1e6,
+                         "algorithmic_bytes_per_launch": avg_bytes}
+        # whole-step algorithmic bytes: attention every step + the score sweep on trigger steps
         pages_scored = 1 if args.cached_scores else wl.budget // wl.block_size     # per row per trigger
         score_bytes = L * Hk * pages_scored * wl.block_size * D * 2 * elem          # per evicting sequence
-        total_bytes = mean_cached * L * args.steps + score_bytes * n_trigger_seqs
-        result["path_GBps"] = total_bytes / elapsed / 1e9
-        result["path_frac_of_hbm_peak"] = result["path_GBps"] / HBM_PEAK_GBS
+        total_bytes = avg_bytes * L * steps + score_bytes * n_trigger_seqs
+        r["path_GBps"] = total_bytes / elapsed / 1e9
+        r["path_frac_of_hbm_peak"] = r["path_GBps"] / HBM_PEAK_GBS
+    r["kernels"] = kernel_breakdown(eng, wl, new_k[0], new_v[0], q[0], out) if breakdown else None
+    del eng, new_k, new_v, q, out
+    torch.cuda.empty_cache()
+    return r
 
-    result["kernels"] = None if (args.graph or args.no_kernel_breakdown) else kernel_breakdown(
-        eng, wl, new_k[0], new_v[0], q[0], out)
+
+def other_configs(synth):
+    """The benchmark configurations besides the headline one, each for a whole number of trigger periods."""
+    long_ = synth.LONG_8B
+    return [("tiny_f32", synth.TINY, 32),
+            ("llama32_1b_C512", synth.LLAMA32_1B.with_(budget=512), 64),
+            ("llama32_1b_C1024", synth.LLAMA32_1B, 64),
+            ("llama32_1b_C2048", synth.LLAMA32_1B.with_(budget=2048), 64),
+            ("llama32_3b", synth.LLAMA32_3B, 64),
+            ("llama31_8b_long_L65536_B16_C4096", long_, 64),
+            ("llama31_8b_long_L131072_B32_C8192", long_.with_(context=(131072,), block_size=32, budget=8192), 64)]
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (rows are independent, the path shards with no collective); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2509_04377_amd import synth
+
+    wl = synth.WORKLOADS[args.workload]
+    if args.budget is not None:
+        wl = wl.with_(budget=args.budget)
+    if args.block_size is not None:
+        wl = wl.with_(block_size=args.block_size)
+    if args.context is not None:
+        wl = wl.with_(context=(args.context,))
+    if args.q_heads is not None:
+        wl = wl.with_(num_q_heads=args.q_heads)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    decode_opts = {}
+    if args.splits is not None:
+        decode_opts["decode_splits"] = args.splits
+    if args.xcd_map is not None:
+        decode_opts["decode_flat_order"] = 1 - args.xcd_map
+    if args.waves is not None or args.depth is not None or args.loads is not None:
+        decode_opts["decode_shape"] = (args.waves or 4) * 100 + (args.depth or 2) * 10 + (args.loads or 2)
+
+    shared = args.layout == "shared"
+    # the committed counter summary covers the workload as defined, in the per-head layout; any override of the
+    # shape changes the bytes, so no measured traffic is quoted then
+    overridden = any(v is not None for v in (args.budget, args.block_size, args.q_heads, args.context)) or args.stagger
+    profile_key = None if overridden else wl.name + ("_shared" if shared else "")
+    m = run_workload(wl, args, dev, args.steps, args.warmup, shared, args.stagger, decode_opts, args.sample_every,
+                     breakdown=not (args.graph or args.no_kernel_breakdown), profile_key=profile_key)
+    result = {
+        "metric": "decode tokens/s (score+evict+paged attn), %s shape" % SHAPE_NAMES.get(wl.name, wl.name),
+        "value": m["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": workload_label(wl), "layout": args.layout, "stagger": args.stagger,
+                   "decode_splits": m["decode_splits"], "fused_append": m["fused_append"],
+                   "cached_scores": args.cached_scores, "fused_evict": args.fused_evict, "hip_graph": args.graph,
+                   "trigger_steps": m["trigger_steps"], "sequence_evictions": m["sequence_evictions"]},
+        "step_ms": m["step_ms"], "prefill_prune": m["prefill_prune"], "roofline": m["roofline"],
+        "path_GBps": m["path_GBps"], "path_frac_of_hbm_peak": m.get("path_frac_of_hbm_peak"), "kernels": m["kernels"],
+    }
+
+    if not args.no_configs:
+        # every other configuration, same driver, default launch shape, a whole number of trigger periods
+        configs = {}
+        for key, cwl, csteps in other_configs(synth):
+            cm = run_workload(cwl, args, dev, csteps, cwl.block_size, False, False, None, 4)
+            rf = cm["roofline"] or {}
+            configs[key] = {"workload": workload_label(cwl), "dtype": cwl.dtype, "tokens_per_s": cm["tokens_per_s"],
+                            "ms_per_step": cm["ms_per_step"], "step_ms_p50": cm["step_ms"]["p50"],
+                            "step_ms_p99": cm["step_ms"]["p99"], "steps": csteps, "trigger_steps": cm["trigger_steps"],
+                            "decode_splits": cm["decode_splits"],
+                            "attention_launch_us": rf.get("avg_launch_us"),
+                            "attention_bytes_per_launch": rf.get("algorithmic_bytes_per_launch"),
+                            "attention_GBps": rf.get("achieved"), "attention_frac_of_hbm_peak": rf.get("frac"),
+                            "path_frac_of_hbm_peak": cm.get("path_frac_of_hbm_peak"),
+                            "prune_ms_per_layer": cm["prefill_prune"]["ms_per_layer"],
+                            "prune_GBps": cm["prefill_prune"]["GBps"],
+                            "prune_frac_of_hbm_peak": cm["prefill_prune"]["frac_of_hbm_peak"]}
+        result["configs"] = configs
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)

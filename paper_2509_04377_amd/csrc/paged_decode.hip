@@ -1,7 +1,7 @@
 // Paged decode attention (Eq. 1 for one new query per sequence; Alg. 3 "PagedAttention(Q,K,V)").
 //
-// A workgroup owns one split of one (sequence, KV head) row: a contiguous range of tiles of the row's
-// tokens.  Each of its four waves walks tiles with a two-deep register pipeline.  Inside a tile every
+// A workgroup owns one split of one (sequence, KV head) row: every splits-th group of four consecutive tiles
+// of the row's tokens.  Each of its four waves walks tiles with a two-deep register pipeline.  Inside a tile every
 // lane holds 16 bytes of four K rows and four V rows (consecutive lanes = consecutive addresses, so
 // each wave-load is 1 KiB of one page, found through the block table with scalar loads).
 //
@@ -323,10 +323,13 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
     nk[0] = load_vec(p.new_k, vec);
     nv[0] = load_vec(p.new_v, vec);
   }
-  // page ids of the tile that is issued next; with one split the wave's first tile is tile `wave`
-  // whatever the row length, so its lookup travels together with the length itself
+  // The row's tiles are dealt out round-robin: tile t belongs to split (t / WAVES) % splits, wave t % WAVES.  A
+  // wave's first tile is therefore the same whatever the row length, and the lookup of its page travels
+  // together with the length itself instead of waiting for it (one dependent round trip to memory less).
+  const int stride = p.splits * WAVES;
+  const int first = split * WAVES + wave;
   int phys[TL::NPT];
-  if (p.splits == 1) TL::lookup(phys, wave, bt, p.max_blocks, p.log2_block);
+  TL::lookup(phys, first, bt, p.max_blocks, p.log2_block);
   const int len_pool = p.seq_lens[s];               // tokens that are read from the pool
   const int len = FUSED ? len_pool + 1 : len_pool;  // tokens attended to
 #pragma unroll
@@ -342,8 +345,6 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
     }
   }
   const int ntiles = (len_pool + TT - 1) / TT;
-  const int t_begin = (int)(((int64_t)split * ntiles) / p.splits);
-  const int t_end = (int)(((int64_t)(split + 1) * ntiles) / p.splits);
 
   float m_run = kNegInf;  // running max of head c_lane over this lane's stream of tokens
   float l_run = 0.f;
@@ -353,14 +354,12 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
 
-  // This wave's tiles are t_begin + wave + i*WAVES, i = 0 .. n_mine-1.  DEPTH register buffers: while
-  // tile i is consumed, tiles i+1 .. i+DEPTH-1 are in flight.
-  const int n_mine = (t_end - t_begin - wave + WAVES - 1) / WAVES;
+  // This wave's tiles are first + i*stride, i = 0 .. n_mine-1.  DEPTH register buffers: while tile i is
+  // consumed, tiles i+1 .. i+DEPTH-1 are in flight.
+  const int n_mine = first < ntiles ? (ntiles - first + stride - 1) / stride : 0;
   if (n_mine > 0) {
     uint4 kb[DEPTH][NLT], vb[DEPTH][NLT];
-    const int first = t_begin + wave;
-    const auto tile_at = [&](int i) { return first + (i < n_mine ? i : n_mine - 1) * WAVES; };
-    if (p.splits != 1) TL::lookup(phys, first, bt, p.max_blocks, p.log2_block);
+    const auto tile_at = [&](int i) { return first + (i < n_mine ? i : n_mine - 1) * stride; };
 #pragma unroll
     for (int d = 0; d < DEPTH - 1; ++d) {
       TL::issue(kb[d], vb[d], tile_at(d), phys, k_pool, v_pool, p.log2_block, d < n_mine ? lane_vec : 0, row_vecs);
@@ -374,7 +373,7 @@ __global__ __launch_bounds__(WAVES * kWave) void paged_decode_kernel(const Decod
                   p.log2_block, ahead < n_mine ? lane_vec : 0, row_vecs);
         TL::lookup(phys, tile_at(ahead + 1), bt, p.max_blocks, p.log2_block);
         if (i + ph < n_mine) {
-          TL::template compute<NLT>(kb[ph], vb[ph], (first + (i + ph) * WAVES) * TT, len_pool, grp, p.scale_log2e, qs,
+          TL::template compute<NLT>(kb[ph], vb[ph], (first + (i + ph) * stride) * TT, len_pool, grp, p.scale_log2e, qs,
                                     m_run, l_run, acc);
         }
       }
