@@ -2,19 +2,19 @@
 // evict the E = max(0, L - C) tokens that come first under (score ascending, index ascending), and
 // write the survivors, order kept, into the row's pages.
 //
-// Four kernels on one stream:
+// Three kernels on one stream:
 //   1. token_scores:  sweep of the packed K/V prompt; S_i = ||V_i||/||K_i|| in fp64, rounded once to
 //                     fp32, stored per KV head as a contiguous run  scores[hk][token].
 //   2. select:        per row, radix select (digits of 12, 10 and 10 bits, most significant first) on the
 //                     fp32 bit patterns (scores are >= +0, so they order like unsigned integers) for the
-//                     E-th smallest score T and the number q of tokens equal to T that must go.
-//   3. chunk_counts:  per row and chunk of 1024 tokens, how many scores are > T and how many == T.
-//   4. gather:        per row and chunk, an index-ordered scan turns those counts into the destination
+//                     E-th smallest score T and the number q of tokens equal to T that must go; then, per
+//                     chunk of 1024 tokens of the row, how many scores are > T and how many == T.
+//   3. gather:        per row and chunk, an index-ordered scan turns those counts into the destination
 //                     of every kept token; token rows are then copied with 16-byte lane accesses.
 // A token is kept iff score > T, or score == T and at least q equal-score tokens precede it.
 //
 // Head-shared mode (one decision per sequence, pages [B][Hk][D]): after kernel 1 the per-head scores are
-// averaged over the heads (head order, fp64, one rounding) into one more score row, and kernels 2-4 run on
+// averaged over the heads (head order, fp64, one rounding) into one more score row, and kernels 2-3 run on
 // that row with the whole (token, all heads) record as the unit that is copied.
 #include "pe_device.h"
 #include "pe_launch.h"
@@ -25,7 +25,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kChunk = 1024;  // tokens per chunk in kernels 3 and 4 (4 per thread)
+constexpr int kChunk = 1024;  // tokens per chunk in the count pass and in the gather (4 per gather thread)
 constexpr int kTokPerThread = kChunk / kThreads;
 constexpr int kSweepLoads = 4;  // token sweep: wave-loads of K (and of V) per step
 constexpr int kSweepIters = 4;  // and steps per wave (8 measured the same)
@@ -129,7 +129,10 @@ __global__ __launch_bounds__(kThreads) void token_scores_kernel(const T* __restr
     const int h = p / ntok;
     const int64_t tok = tok_lo + (p - h * ntok);
     const int64_t r = tok * num_kv_heads + h;
-    if (r >= group_row0 && r < group_end) scores[(int64_t)h * total_tokens + tok] = sm_score[(int)(r - group_row0)];
+    // non-temporal: the scores are written once and read by another kernel (measured 330 us against 344 us per
+    // 2.1 GB swept with plain stores; with no stores at all the sweep takes 316 us)
+    if (r >= group_row0 && r < group_end)
+      __builtin_nontemporal_store(sm_score[(int)(r - group_row0)], &scores[(int64_t)h * total_tokens + tok]);
   }
 }
 
@@ -144,25 +147,66 @@ __global__ __launch_bounds__(kThreads) void head_mean_kernel(const float* __rest
   mean_out[t] = (float)(sum / (double)num_kv_heads);
 }
 
-// ---- 2. per-row radix select ------------------------------------------------------------------------
-// One workgroup of 1024 threads per row; three passes over the row's fp32 bit patterns, most significant
-// digit first: 12 bits (sign, exponent, top three mantissa bits: scores of one row cluster in a few
-// exponents, and a narrower first digit would pile every LDS atomic onto three or four bins), then
-// 10 + 10 bits.  After a pass the digit that holds rank k is found with a workgroup-wide scan.
+// ---- 2. per-row radix select + per-chunk counts ------------------------------------------------------
+// One workgroup of 1024 threads per row.  Radix select on the row's fp32 bit patterns, most significant digit
+// first: 12 bits (sign, exponent, top three mantissa bits: scores of one row cluster in a few exponents, and a
+// narrower first digit would pile every LDS atomic onto three or four bins), then 10 + 10 bits.  After a pass
+// the digit that holds rank k is found with a workgroup-wide scan.  The first pass reads the whole row with
+// 16-byte loads, eight in flight per thread.  The tokens that fall into the first digit's bin are then
+// collected in LDS (a few percent of the row for any spread-out score distribution), so the second and third
+// pass never touch memory; a row with more candidates than the LDS buffer holds (e.g. all scores equal) falls
+// back to passes over memory.  With the threshold known the same workgroup counts, per chunk of 1024 tokens,
+// how many scores are > T and how many == T (one wave per chunk): the gather turns these into destinations.
+// A row is worked on by one compute unit; what bounds a pass over a long row is that unit's instruction issue
+// (about ten instructions per token), not memory: a finer first digit (16384 bins) was measured and changed
+// nothing, and spreading a row over several workgroups needs a launch per digit and per merge, which costs
+// more than it saves at these row lengths.
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kSelBins = 4096;
 constexpr int kSelUnroll = 8;
+constexpr int kSelCand = 8192;  // candidates kept in LDS after the first pass (32 KiB)
+
+// f(bits) for every element of bits[0 .. L): a scalar head up to 16-byte alignment, 16-byte loads with
+// kSelUnroll in flight per thread, a scalar tail.  The order of visits is unspecified.
+template <typename F>
+__device__ __forceinline__ void visit_row(const uint32_t* bits, int L, int tid, F f) {
+  int mis = (int)((4u - (uint32_t)((reinterpret_cast<uintptr_t>(bits) >> 2) & 3u)) & 3u);
+  mis = mis < L ? mis : L;
+  if (tid < mis) f(bits[tid]);
+  const uint4* v = reinterpret_cast<const uint4*>(bits + mis);
+  const int nvec = (L - mis) >> 2;
+  for (int base = tid; base < nvec; base += kSelUnroll * kSelThreads) {
+    uint4 r[kSelUnroll];
+#pragma unroll
+    for (int j = 0; j < kSelUnroll; ++j) {
+      const int i = base + j * kSelThreads;
+      r[j] = v[i < nvec ? i : nvec - 1];
+    }
+#pragma unroll
+    for (int j = 0; j < kSelUnroll; ++j) {
+      if (base + j * kSelThreads < nvec) {
+        f(r[j].x);
+        f(r[j].y);
+        f(r[j].z);
+        f(r[j].w);
+      }
+    }
+  }
+  const int tail0 = mis + nvec * 4;
+  if (tail0 + tid < L) f(bits[tail0 + tid]);
+}
 
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores,
                                                              const int32_t* __restrict__ cu_seqlens,
-                                                             uint32_t* __restrict__ sel,
+                                                             uint32_t* __restrict__ sel, int32_t* __restrict__ cnt,
                                                              int32_t* __restrict__ seq_lens_out,
                                                              int32_t* __restrict__ kept_idx_out, int64_t total_tokens,
-                                                             int num_kv_heads, int budget) {
+                                                             int64_t chunk_slots, int num_kv_heads, int budget) {
   __shared__ uint32_t hist[kSelBins];
+  __shared__ uint32_t cand[kSelCand];
   __shared__ uint32_t wave_tot[kSelWaves];
-  __shared__ uint32_t sh_prefix, sh_k;
+  __shared__ uint32_t sh_prefix, sh_k, sh_ncand;
   const int row = (int)blockIdx.x;
   const int s = row / num_kv_heads, h = row % num_kv_heads;
   const int t0 = cu_seqlens[s];
@@ -177,75 +221,112 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
   if (kept_idx_out != nullptr)
     for (int i = keep + tid; i < budget; i += kSelThreads) kept_idx_out[(int64_t)row * budget + i] = -1;
 
-  if (E == 0) {  // nothing to evict: T = +0.0, q = 0 keeps every token (scores are >= +0)
-    if (tid == 0) {
-      sel[2 * row] = 0u;
-      sel[2 * row + 1] = 0u;
-    }
-    return;
-  }
+  // E == 0, nothing to evict: T = +0.0, q = 0 keeps every token (scores are >= +0)
   uint32_t prefix = 0u, mask = 0u;
-  uint32_t k = (uint32_t)(E - 1);  // 0-based rank of the threshold element among the remaining ones
+  uint32_t k = (uint32_t)(E > 0 ? E - 1 : 0);  // 0-based rank of the threshold element among the remaining ones
+  bool in_lds = false;                         // the remaining candidates are cand[0 .. ncand)
+  uint32_t ncand = 0u;
+  if (E > 0) {
 #pragma unroll 1
-  for (int pass = 0; pass < 3; ++pass) {
-    const int shift = pass == 0 ? 20 : pass == 1 ? 10 : 0;
-    const int nbins = pass == 0 ? 4096 : 1024;
-    const int per_thread = nbins / kSelThreads;  // 4 or 1 consecutive bins per thread
-    for (int i = tid; i < nbins; i += kSelThreads) hist[i] = 0u;
-    __syncthreads();
-    // eight loads in flight per thread: the LDS atomics would otherwise serialise the loop on load latency
-    for (int base = tid; base < L; base += kSelUnroll * kSelThreads) {
-      uint32_t b[kSelUnroll];
-#pragma unroll
-      for (int j = 0; j < kSelUnroll; ++j) {
-        const int i = base + j * kSelThreads;
-        b[j] = bits[i < L ? i : L - 1];
-      }
-#pragma unroll
-      for (int j = 0; j < kSelUnroll; ++j) {
-        const int i = base + j * kSelThreads;
-        if (i < L && (b[j] & mask) == prefix) atomicAdd(&hist[(b[j] >> shift) & (uint32_t)(nbins - 1)], 1u);
-      }
-    }
-    __syncthreads();
-    // workgroup-wide exclusive scan of the per-thread bin totals, in bin order
-    uint32_t c[4] = {0u, 0u, 0u, 0u}, tot = 0u;
-    for (int j = 0; j < per_thread; ++j) {
-      c[j] = hist[tid * per_thread + j];
-      tot += c[j];
-    }
-    uint32_t incl = tot;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      const uint32_t o = (uint32_t)__shfl_up((int)incl, off, kWave);
-      if (lane >= off) incl += o;
-    }
-    if (lane == kWave - 1) wave_tot[wave] = incl;
-    __syncthreads();
-    uint32_t before = incl - tot;
-    for (int w = 0; w < wave; ++w) before += wave_tot[w];
-    if (k >= before && k < before + tot) {  // exactly one thread: rank k falls into one of its bins
-      for (int j = 0; j < per_thread; ++j) {
-        if (k >= before && k < before + c[j]) {
-          sh_prefix = prefix | ((uint32_t)(tid * per_thread + j) << shift);
-          sh_k = k - before;
+    for (int pass = 0; pass < 3; ++pass) {
+      const int shift = pass == 0 ? 20 : pass == 1 ? 10 : 0;
+      const int nbins = pass == 0 ? kSelBins : 1024;
+      constexpr int kMaxPerThread = kSelBins / kSelThreads;
+      const int per_thread = nbins / kSelThreads;  // 4 or 1 consecutive bins per thread
+      for (int i = tid; i < nbins; i += kSelThreads) hist[i] = 0u;
+      __syncthreads();
+      const uint32_t bmask = (uint32_t)(nbins - 1);
+      if (in_lds) {
+        for (uint32_t i = (uint32_t)tid; i < ncand; i += kSelThreads) {
+          const uint32_t b = cand[i];
+          if ((b & mask) == prefix) atomicAdd(&hist[(b >> shift) & bmask], 1u);
         }
-        before += c[j];
+      } else {
+        visit_row(bits, L, tid, [&](uint32_t b) {
+          if ((b & mask) == prefix) atomicAdd(&hist[(b >> shift) & bmask], 1u);
+        });
+      }
+      __syncthreads();
+      // workgroup-wide exclusive scan of the per-thread bin totals, in bin order
+      uint32_t c[kMaxPerThread], tot = 0u;
+#pragma unroll
+      for (int j = 0; j < kMaxPerThread; ++j) {
+        const int bin = tid * per_thread + j;
+        c[j] = (j < per_thread && bin < nbins) ? hist[bin] : 0u;
+        tot += c[j];
+      }
+      uint32_t incl = tot;
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_up((int)incl, off, kWave);
+        if (lane >= off) incl += o;
+      }
+      if (lane == kWave - 1) wave_tot[wave] = incl;
+      __syncthreads();
+      uint32_t before = incl - tot;
+      for (int w = 0; w < wave; ++w) before += wave_tot[w];
+      if (k >= before && k < before + tot) {  // exactly one thread: rank k falls into one of its bins
+#pragma unroll
+        for (int j = 0; j < kMaxPerThread; ++j) {
+          if (k >= before && k < before + c[j]) {
+            sh_prefix = prefix | ((uint32_t)(tid * per_thread + j) << shift);
+            sh_k = k - before;
+            sh_ncand = c[j];
+          }
+          before += c[j];
+        }
+      }
+      __syncthreads();
+      prefix = sh_prefix;
+      k = sh_k;
+      const uint32_t in_bin = sh_ncand;
+      mask |= bmask << shift;
+      __syncthreads();
+      if (pass == 0 && in_bin <= (uint32_t)kSelCand) {
+        // collect the tokens of the chosen bin in LDS (their order does not matter: only values are counted)
+        if (tid == 0) sh_ncand = 0u;
+        __syncthreads();
+        visit_row(bits, L, tid, [&](uint32_t b) {
+          if ((b & mask) == prefix) cand[atomicAdd(&sh_ncand, 1u)] = b;
+        });
+        __syncthreads();
+        ncand = sh_ncand;  // == in_bin
+        in_lds = true;
+        __syncthreads();
       }
     }
-    __syncthreads();
-    prefix = sh_prefix;
-    k = sh_k;
-    mask |= (uint32_t)(nbins - 1) << shift;
-    __syncthreads();
   }
+  const uint32_t T = prefix;                         // threshold score (bit pattern)
   if (tid == 0) {
-    sel[2 * row] = prefix;     // T
-    sel[2 * row + 1] = k + 1;  // q: the first q tokens (index order) with score == T are evicted
+    sel[2 * row] = T;
+    sel[2 * row + 1] = E > 0 ? k + 1 : 0u;           // q: the first q tokens (index order) with score == T go
+  }
+
+  // per-chunk counts, one wave per chunk: 16 tokens per lane, all loads issued before the first compare
+  const int nchunks = (L + kChunk - 1) / kChunk;
+  int32_t* crow = cnt + ((int64_t)h * chunk_slots + chunk_slot(t0, s, 0)) * 2;
+  for (int c = wave; c < nchunks; c += kSelWaves) {
+    constexpr int kPerLane = kChunk / kWave;
+    uint32_t b[kPerLane];
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+      const int i = c * kChunk + j * kWave + lane;
+      b[j] = bits[i < L ? i : L - 1];
+    }
+    int gt = 0, eq = 0;
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+      const bool in = c * kChunk + j * kWave + lane < L;
+      gt += __popcll(__builtin_amdgcn_ballot_w64(in && b[j] > T));
+      eq += __popcll(__builtin_amdgcn_ballot_w64(in && b[j] == T));
+    }
+    if (lane == 0) {
+      crow[2 * c] = gt;
+      crow[2 * c + 1] = eq;
+    }
   }
 }
 
-// ---- 3. per-chunk counts ------------------------------------------------------------------------------
 __device__ __forceinline__ int block_sum(int v, int* sh /* [kWaves] */) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
@@ -259,41 +340,7 @@ __device__ __forceinline__ int block_sum(int v, int* sh /* [kWaves] */) {
   return t;
 }
 
-__global__ __launch_bounds__(kThreads) void chunk_counts_kernel(const float* __restrict__ scores,
-                                                                const int32_t* __restrict__ cu_seqlens,
-                                                                const uint32_t* __restrict__ sel,
-                                                                int32_t* __restrict__ cnt, int64_t total_tokens,
-                                                                int64_t chunk_slots, int num_kv_heads,
-                                                                int chunks_per_row) {
-  __shared__ int sh[kWaves];
-  const int row = (int)(blockIdx.x / chunks_per_row);
-  const int chunk = (int)(blockIdx.x % chunks_per_row);
-  const int s = row / num_kv_heads, h = row % num_kv_heads;
-  const int t0 = cu_seqlens[s];
-  const int L = cu_seqlens[s + 1] - t0;
-  if (chunk * kChunk >= L) return;
-  const uint32_t T = sel[2 * row];
-  const uint32_t* bits = reinterpret_cast<const uint32_t*>(scores) + (int64_t)h * total_tokens + t0;
-  int gt = 0, eq = 0;
-#pragma unroll
-  for (int j = 0; j < kTokPerThread; ++j) {
-    const int i = chunk * kChunk + (int)threadIdx.x * kTokPerThread + j;
-    if (i < L) {
-      const uint32_t b = bits[i];
-      gt += b > T;
-      eq += b == T;
-    }
-  }
-  gt = block_sum(gt, sh);
-  eq = block_sum(eq, sh);
-  if (threadIdx.x == 0) {
-    int32_t* c = cnt + ((int64_t)h * chunk_slots + chunk_slot(t0, s, chunk)) * 2;
-    c[0] = gt;
-    c[1] = eq;
-  }
-}
-
-// ---- 4. gather ----------------------------------------------------------------------------------------
+// ---- 3. gather ----------------------------------------------------------------------------------------
 // VPR_T > 0: vectors per token row known at compile time; 0: taken from vpr_rt (head-shared mode, where a
 // row is the K (or V) of all heads of a token).
 template <int VPR_T>
@@ -435,7 +482,7 @@ hipError_t launch(const PruneArgs& a, hipStream_t stream) {
                        (const T*)a.k_in, (const T*)a.v_in, w.scores, total_rows, a.total_tokens, a.num_kv_heads);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  // what kernels 2-4 see: per-head rows, or (shared) one row per sequence whose score is the head mean and
+  // what kernels 2-3 see: per-head rows, or (shared) one row per sequence whose score is the head mean and
   // whose record is the token's K (or V) of all heads
   const int heads = a.shared ? 1 : a.num_kv_heads;
   const float* sel_scores = w.scores;
@@ -451,15 +498,12 @@ hipError_t launch(const PruneArgs& a, hipStream_t stream) {
   }
   const int rows = a.num_seqs * heads;
   hipLaunchKernelGGL(select_kernel, dim3((unsigned)rows), dim3(kSelThreads), 0, stream, sel_scores, a.cu_seqlens,
-                     w.sel, a.seq_lens_out, a.kept_idx_out, a.total_tokens, heads, a.budget);
+                     w.sel, w.cnt, a.seq_lens_out, a.kept_idx_out, a.total_tokens, w.chunk_slots, heads, a.budget);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const int chunks_per_row = (a.max_seqlen + kChunk - 1) / kChunk;
   if (chunks_per_row == 0) return hipSuccess;
   const int64_t grid2 = (int64_t)rows * chunks_per_row;
   if (grid2 > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(chunk_counts_kernel, dim3((unsigned)grid2), dim3(kThreads), 0, stream, sel_scores, a.cu_seqlens,
-                     w.sel, w.cnt, a.total_tokens, w.chunk_slots, heads, chunks_per_row);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
   constexpr int VPR = G::kLanesPerRow;
   if (a.shared) {
     hipLaunchKernelGGL((gather_kernel<0>), dim3((unsigned)grid2), dim3(kThreads), 0, stream, (const uint4*)a.k_in,
