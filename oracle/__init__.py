@@ -25,9 +25,17 @@ _i32p = ctypes.POINTER(ctypes.c_int32)
 def _load():
     global _lib
     if _lib is None:
-        # PE_ORACLE_LIB: a test (tests/test_oracle_mutants.py) points this at a deliberately broken build of
-        # the oracle to check that the pins notice; nothing else sets it
-        path = os.environ.get("PE_ORACLE_LIB") or _build.build(force=False)
+        # PE_ORACLE_LIB: tests/test_oracle_mutants.py points its child processes at a deliberately broken
+        # build of the oracle to check that the pins notice.  It is honoured only together with the marker
+        # that test sets (PE_ORACLE_MUTANT_RUN=1) and never in a process that has a GPU test selected
+        # (tests/conftest.py refuses to start a GPU run with it); set alone it is an error, not a silent swap.
+        path = os.environ.get("PE_ORACLE_LIB")
+        if path:
+            if os.environ.get("PE_ORACLE_MUTANT_RUN") != "1":
+                raise RuntimeError("PE_ORACLE_LIB is set outside the oracle mutation test: refusing to load a "
+                                   "substitute oracle (%s)" % path)
+        else:
+            path = _build.build(force=False, sanitize=os.environ.get("PE_ORACLE_SANITIZE") == "1")
         lib = ctypes.CDLL(path)
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_token_ratio.restype = ctypes.c_double

@@ -120,7 +120,7 @@ def _kill(case, tmp):
     lib = os.path.join(tmp, tag + ".so")
     subprocess.run(["gcc", "-std=c11", "-O1", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off", "-w", "-o", lib] + paths +
                    ["-lm"], check=True)
-    env = dict(os.environ, PE_ORACLE_LIB=lib, OMP_NUM_THREADS="2")
+    env = dict(os.environ, PE_ORACLE_LIB=lib, PE_ORACLE_MUTANT_RUN="1", OMP_NUM_THREADS="2")
     target = os.path.join(ROOT, "tests", "test_oracle_%s.py" % pins)
     r = subprocess.run([sys.executable, "-m", "pytest", target, "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider"],
                        cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
