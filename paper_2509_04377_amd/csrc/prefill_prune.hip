@@ -157,10 +157,11 @@ __global__ __launch_bounds__(kThreads) void head_mean_kernel(const float* __rest
 // pass never touch memory; a row with more candidates than the LDS buffer holds (e.g. all scores equal) falls
 // back to passes over memory.  With the threshold known the same workgroup counts, per chunk of 1024 tokens,
 // how many scores are > T and how many == T (one wave per chunk): the gather turns these into destinations.
-// A row is worked on by one compute unit; what bounds a pass over a long row is that unit's instruction issue
-// (about ten instructions per token), not memory: a finer first digit (16384 bins) was measured and changed
-// nothing, and spreading a row over several workgroups needs a launch per digit and per merge, which costs
-// more than it saves at these row lengths.
+// A row is worked on by one compute unit, and one compute unit pulls about 45 GB/s from L2 however many loads
+// it keeps in flight: that, not the histogram atomics, bounds a pass over a long row (a finer first digit of
+// 16384 bins was measured and changed nothing).  Spreading a row over several workgroups needs a launch per
+// stage (pivots, counting pass, exact selection, chunk counts), which costs most of what it saves at these
+// row lengths.
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kSelBins = 4096;
