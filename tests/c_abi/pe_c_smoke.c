@@ -99,6 +99,26 @@ int main(void) {
     }
   }
 
+  /* (4) again with the row split in two (per-descriptor launch shape) and through the entry point that needs no
+     workspace: the same output within rounding */
+  {
+    pe_cache_desc split = desc;
+    split.decode_splits = 2;
+    if (pe_decode_splits(&split) != 2 || pe_decode_splits(&desc) < 1) return 1;
+    if (pe_workspace_bytes(PE_OP_PAGED_DECODE, &split, 0) != (size_t)S * HQ * 2 * (D + 2) * sizeof(float)) return 1;
+    float* d_out2;
+    CHECK_HIP(hipMalloc((void**)&d_out2, sizeof(float) * S * HQ * D));
+    CHECK_PE(pe_paged_decode_static(&split, d_q, d_k, d_v, d_table, d_len, 0.125f, d_out2, stream));
+    float h_out2[S * HQ * D];
+    CHECK_HIP(hipStreamSynchronize(stream));
+    CHECK_HIP(hipMemcpy(h_out2, d_out2, sizeof(h_out2), hipMemcpyDeviceToHost));
+    for (int i = 0; i < S * HQ * D; ++i)
+      if (fabs(h_out2[i] - h_out[i]) > 1e-5 * (1.0 + fabs(h_out[i]))) {
+        fprintf(stderr, "split/static out[%d] = %g, want %g\n", i, h_out2[i], h_out[i]);
+        return 1;
+      }
+  }
+
   /* (3) eviction from given scores: 3 1 2 1 -> logical page 1 */
   const float given[MAXB] = {3.f, 1.f, 2.f, 1.f, INFINITY};
   for (int h = 0; h < HK; ++h) memcpy(h_scores + h * MAXB, given, sizeof(given));

@@ -393,6 +393,27 @@ def test_prefill_prune_ties():
     assert np.array_equal(kept[0, 0], np.arange(2100 - 512, 2100))
 
 
+def test_prefill_prune_crowded_threshold_bin():
+    """Rows whose scores crowd into one bin of the selection's first radix digit, more of them than its LDS
+    candidate buffer holds (8192): the later digits are then resolved by passes over memory.  (a) all scores equal
+    (V = K), rows of 20000 and 9001 tokens starting at offsets that are not multiples of four scores; (b) fp32 rows
+    with V = K * c, c spread over [1, 1.1): one first-digit bin, distinct lower digits; (c) a mix in which the
+    threshold bin is crowded and other bins are populated too."""
+    print("case prefill_prune_crowded_bin", flush=True)
+    lens = [3, 20000, 9001, 1022]
+    k, _, cu = _prompt(620, lens, 2, 64, torch.bfloat16)
+    kept = _prune_both(k, k.clone(), cu, lens, 2, 64, 16, 1024, torch.bfloat16, 621)          # (a)
+    assert np.array_equal(kept[1, 0], np.arange(20000 - 1024, 20000))
+    assert np.array_equal(kept[2, 1], np.arange(9001 - 1024, 9001))
+    g = torch.Generator().manual_seed(622)
+    lens = [17000, 5]
+    k, _, cu = _prompt(623, lens, 2, 64, torch.float32)
+    c = 1.0 + 0.1 * torch.rand((sum(lens), 2, 1), generator=g)
+    _prune_both(k, (k * c).contiguous(), cu, lens, 2, 64, 32, 2048, torch.float32, 624)       # (b)
+    c[::3] = torch.exp(torch.randn((c[::3].shape[0], 2, 1), generator=g))                     # (c) a third elsewhere
+    _prune_both(k, (k * c).contiguous(), cu, lens, 2, 64, 32, 4096, torch.float32, 625)
+
+
 def test_append_kv_matches_oracle():
     print("case append_kv", flush=True)
     Hk, D, B = 3, 64, 16
