@@ -51,7 +51,7 @@ def parse_args():
                     help="keep page scores across steps and score only newly filled pages (not the paper's stated "
                          "procedure; the score sweep then drops out of the byte count too)")
     ap.add_argument("--fused-evict", action="store_true",
-                    help="score + evict of a trigger step in one launch (pe_score_evict)")
+                    help="score + evict of a trigger step in one pass over the pages (pe_score_evict)")
     ap.add_argument("--layout", choices=("per_head", "shared"), default="per_head",
                     help="shared: one block-table row and one eviction decision per sequence, pages [B, Hk, D] "
                          "(separate append and attention launches)")

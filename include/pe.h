@@ -201,13 +201,15 @@ int pe_score_triggered_blocks(const pe_cache_desc* desc, const void* k_pool, con
                               float* scores_inout, void* stream);
 
 /*
- * (1)+(3) in one launch -- the whole "if L % B == 0" branch of Alg. 3.  Equal in effect to pe_score_blocks
- * followed by pe_evict_blocks, except that only triggering sequences are scored: their rows' pages are swept
- * once, the running minimum is kept (ties: lowest index), the table row is compacted and seq_lens[s] -= B.
+ * (1)+(3) in one pass over the pages -- the whole "if L % B == 0" branch of Alg. 3.  Equal in effect to
+ * pe_score_blocks followed by pe_evict_blocks, except that only triggering sequences are scored: their rows' pages
+ * are swept once (one workgroup per row, so a few evicting sequences use the chip as well as a whole batch), the
+ * running minimum is kept (ties: lowest index), the table row is compacted, and a second, tiny launch behind the
+ * sweep sets seq_lens[s] -= B (every row of a sequence has to see the length from before the eviction).  No score
+ * array travels through memory unless asked for.
  * scores_out: NULL, or [S][Hk][max_blocks] fp32; rows of triggering sequences receive the scores the decision
  * was taken on (before compaction; entries j >= seq_lens[s]/B are +INF), rows of other sequences are left
- * untouched.  evicted_logical_out / freed_phys_out as in (3).  One workgroup per sequence: efficient when most
- * sequences of the batch trigger together, short of parallelism when only a few do (use the two calls then).
+ * untouched.  evicted_logical_out / freed_phys_out as in (3).
  */
 int pe_score_evict(const pe_cache_desc* desc, const void* k_pool, const void* v_pool, int32_t* block_table,
                    int32_t* seq_lens, int32_t budget_tokens, float* scores_out, int32_t* evicted_logical_out,

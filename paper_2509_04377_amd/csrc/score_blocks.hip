@@ -141,15 +141,19 @@ __global__ __launch_bounds__(kThreads) void score_blocks_kernel(const T* __restr
   }
 }
 
-// Score and evict in one launch (Alg. 3, the whole "L % B == 0" branch): one workgroup per sequence, one wave
-// per row at a time.  The wave sweeps the row's pages in logical order with a two-deep register pipeline,
-// keeps the running minimum (a strictly lower score replaces it, so ties stay with the lowest index), then
-// compacts the table row.  Scores are also written out when the caller wants them.
+// Score and evict in one pass over the pages (Alg. 3, the whole "L % B == 0" branch): one workgroup per ROW, so
+// the launch fills the chip whether all sequences of a batch evict together or only a few do.  Wave w of the
+// workgroup sweeps the row's pages w, w + 4, ... in logical order with a two-deep register pipeline and the same
+// per-page arithmetic as the sweep above, and keeps its running minimum (a strictly lower score replaces it, so
+// ties stay with the lowest index); the four minima are merged lexicographically by (score, index) and wave 0
+// compacts the table row.  Scores are also written out when the caller wants them.  The kernel only READS
+// seq_lens: every row of a sequence must see the length from before the eviction, so the lengths are updated by
+// score_evict_lens_kernel, launched right behind it.
 template <typename T, int D, int B>
 __global__ __launch_bounds__(kThreads) void score_evict_kernel(const T* __restrict__ k_pool,
                                                                const T* __restrict__ v_pool,
                                                                int32_t* __restrict__ block_table,
-                                                               int32_t* __restrict__ seq_lens,
+                                                               const int32_t* __restrict__ seq_lens,
                                                                float* __restrict__ scores_out,
                                                                int32_t* __restrict__ evicted_logical,
                                                                int32_t* __restrict__ freed_phys, int num_kv_heads,
@@ -158,49 +162,53 @@ __global__ __launch_bounds__(kThreads) void score_evict_kernel(const T* __restri
   using CS = typename PG::CS;
   constexpr int NL = CS::NL;
   constexpr int NCH = PG::NCH;
-  const int s = (int)blockIdx.x;
+  __shared__ float sm_best[kWaves];
+  __shared__ int sm_j[kWaves];
+  const int64_t row = (int64_t)blockIdx.x;
+  const int s = (int)(row / num_kv_heads);
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   const int len = seq_lens[s];
   const int n = len / B;
   const bool trigger = len > 0 && (len % B) == 0 && len >= budget && n <= max_blocks;
-
-  for (int h = wave; h < num_kv_heads; h += kWaves) {
-    const int64_t row = (int64_t)s * num_kv_heads + h;
-    if (!trigger) {
-      if (lane == 0) {
-        evicted_logical[row] = -1;
-        freed_phys[row] = -1;
-      }
-      continue;
+  if (!trigger) {  // workgroup-uniform
+    if (threadIdx.x == 0) {
+      evicted_logical[row] = -1;
+      freed_phys[row] = -1;
     }
-    int32_t* bt = block_table + row * max_blocks;
-    float* out = scores_out != nullptr ? scores_out + row * max_blocks : nullptr;
-    uint4 kb[2][NL], vb[2][NL];
-    float best = 0.f;
-    int jstar = 0;
-    double sum = 0.0;
-    const int units = n * NCH;  // (page, chunk) units in logical order; unit u = page u / NCH, chunk u % NCH
-    // a page is complete after its last chunk: round once, compare, report
-    auto page_done = [&](int u) {
-      if (u % NCH != NCH - 1) return;
-      const int j = u / NCH;
-      const float sc = (float)(sum / (double)B);
-      sum = 0.0;
-      if (j == 0 || sc < best) {
-        best = sc;
-        jstar = j;
-      }
-      if (out != nullptr && lane == 0) out[j] = sc;
-    };
-    // unconditional issues (those past the end re-read the row's last unit) keep the load order known
-    auto issue_unit = [&](int buf, int u) {
-      const int uc = u < units ? u : units - 1;
-      if (buf == 0)
-        CS::issue(kb[0], vb[0], k_pool, v_pool, PG::chunk_base(bt[uc / NCH], uc % NCH), lane);
-      else
-        CS::issue(kb[1], vb[1], k_pool, v_pool, PG::chunk_base(bt[uc / NCH], uc % NCH), lane);
-    };
+    return;
+  }
+  int32_t* bt = block_table + row * max_blocks;
+  float* out = scores_out != nullptr ? scores_out + row * max_blocks : nullptr;
+  uint4 kb[2][NL], vb[2][NL];
+  float best = __builtin_inff();
+  int jstar = 0x7fffffff;  // this wave has seen no page yet
+  double sum = 0.0;
+  // this wave's (page, chunk) units in logical order: unit u = page wave + (u / NCH) * kWaves, chunk u % NCH
+  const int pages_mine = wave < n ? (n - wave + kWaves - 1) / kWaves : 0;
+  const int units = pages_mine * NCH;
+  const auto page_of = [&](int u) { return wave + (u / NCH) * kWaves; };
+  // a page is complete after its last chunk: round once, compare, report
+  auto page_done = [&](int u) {
+    if (u % NCH != NCH - 1) return;
+    const int j = page_of(u);
+    const float sc = (float)(sum / (double)B);
+    sum = 0.0;
+    if (jstar == 0x7fffffff || sc < best) {
+      best = sc;
+      jstar = j;
+    }
+    if (out != nullptr && lane == 0) out[j] = sc;
+  };
+  // unconditional issues (those past the end re-read the wave's last unit) keep the load order known
+  auto issue_unit = [&](int buf, int u) {
+    const int uc = u < units ? u : units - 1;
+    if (buf == 0)
+      CS::issue(kb[0], vb[0], k_pool, v_pool, PG::chunk_base(bt[page_of(uc)], uc % NCH), lane);
+    else
+      CS::issue(kb[1], vb[1], k_pool, v_pool, PG::chunk_base(bt[page_of(uc)], uc % NCH), lane);
+  };
+  if (units > 0) {
     issue_unit(0, 0);
     for (int u = 0; u < units; u += 2) {
       issue_unit(1, u + 1);
@@ -212,17 +220,45 @@ __global__ __launch_bounds__(kThreads) void score_evict_kernel(const T* __restri
         page_done(u + 1);
       }
     }
-    if (out != nullptr)
-      for (int j = n + lane; j < max_blocks; j += kWave) out[j] = __builtin_inff();
-    __builtin_amdgcn_s_waitcnt(0);  // the trailing re-reads have landed before the row moves
-    const int freed = compact_row(bt, nullptr, jstar, n, lane);
+  }
+  if (out != nullptr)
+    for (int j = n + (int)threadIdx.x; j < max_blocks; j += kThreads) out[j] = __builtin_inff();
+  __builtin_amdgcn_s_waitcnt(0);  // this wave's trailing re-reads (pages and table entries) have landed
+  if (lane == 0) {
+    sm_best[wave] = best;
+    sm_j[wave] = jstar;
+  }
+  __syncthreads();  // every wave is done with the table row before wave 0 moves it
+  if (wave == 0) {
+    float bsc = sm_best[0];
+    int bj = sm_j[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {
+      const float osc = sm_best[w];
+      const int oj = sm_j[w];
+      // a wave that saw no page carries index 0x7fffffff and never wins; a NaN score never compares lower
+      if (oj != 0x7fffffff && (bj == 0x7fffffff || osc < bsc || (osc == bsc && oj < bj))) {
+        bsc = osc;
+        bj = oj;
+      }
+    }
+    if (bj == 0x7fffffff || bj >= n) bj = 0;  // n >= 1 here, so wave 0 always holds page 0: defensive only
+    const int freed = compact_row(bt, nullptr, bj, n, lane);
     if (lane == 0) {
-      evicted_logical[row] = jstar;
+      evicted_logical[row] = bj;
       freed_phys[row] = freed;
     }
   }
-  __syncthreads();
-  if (threadIdx.x == 0 && trigger) seq_lens[s] = len - B;
+}
+
+// The length update of pe_score_evict: one thread per sequence, the same trigger predicate on the old length.
+__global__ __launch_bounds__(kThreads) void score_evict_lens_kernel(int32_t* __restrict__ seq_lens, int num_seqs,
+                                                                    int block_size, int max_blocks, int budget) {
+  const int s = (int)(blockIdx.x * kThreads + threadIdx.x);
+  if (s >= num_seqs) return;
+  const int len = seq_lens[s];
+  const int n = len / block_size;
+  if (len > 0 && (len % block_size) == 0 && len >= budget && n <= max_blocks) seq_lens[s] = len - block_size;
 }
 
 template <typename T, int D, int B>
@@ -240,9 +276,15 @@ hipError_t launch(const ScoreArgs& a, hipStream_t stream) {
 
 template <typename T, int D, int B>
 hipError_t launch_fused(const ScoreEvictArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL((score_evict_kernel<T, D, B>), dim3((unsigned)a.num_seqs), dim3(kThreads), 0, stream,
+  const int64_t rows = (int64_t)a.num_seqs * a.num_kv_heads;
+  if (rows <= 0 || rows > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((score_evict_kernel<T, D, B>), dim3((unsigned)rows), dim3(kThreads), 0, stream,
                      (const T*)a.k_pool, (const T*)a.v_pool, a.block_table, a.seq_lens, a.scores_out,
                      a.evicted_logical, a.freed_phys, a.num_kv_heads, a.max_blocks, a.budget);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(score_evict_lens_kernel, dim3((unsigned)((a.num_seqs + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                     stream, a.seq_lens, a.num_seqs, a.block_size, a.max_blocks, a.budget);
   return hipGetLastError();
 }
 

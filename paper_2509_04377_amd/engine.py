@@ -49,7 +49,7 @@ class PagedCache:
     cached_scores: bool = False    # keep `scores` alive across steps and score only newly filled pages
     host_scored: list = None       # per sequence: full pages whose score is in `scores` (host bookkeeping)
     evict_opts: pe.pe_evict_opts = None  # eviction variant (policy, protected pages, shared heads); None = Alg. 3
-    fused_evict: bool = False  # score + evict of a trigger step in one launch (pe.pe_score_evict)
+    fused_evict: bool = False  # score + evict of a trigger step in one pass over the pages (pe_score_evict)
 
     @staticmethod
     def create(dtype, num_seqs, num_kv_heads, num_q_heads, head_dim, block_size, layout, budget, device="cuda",

@@ -45,7 +45,7 @@ def run_loop(wl, steps, layer=0, check_pool=True, fused=True, cached_scores=Fals
     gcache.prefill_prune(k_in.to(DEV), v_in.to(DEV), cu.to(DEV), max(lens), kept)
     gcache.set_host_lens(lens)
     gcache.cached_scores = cached_scores
-    gcache.fused_evict = fused_evict  # decisions only: the one-launch form is not asked for the scores here
+    gcache.fused_evict = fused_evict  # decisions only: the one-pass form is not asked for the scores here
     if evict_opts is not None:
         gcache.evict_opts = pe.pe_evict_opts(evict_opts.get("policy", 0), evict_opts.get("protect_first", 0),
                                              evict_opts.get("protect_last", 0), int(evict_opts.get("share_heads", False)), 0)
@@ -326,11 +326,11 @@ def _oracle_layer_state(wl, lens, k_in, v_in, cu, layout, l, shared):
 @pytest.mark.parametrize("shared,stagger", [(False, False), (False, True), (True, False), (True, True)])
 def test_all_driver_modes_agree_at_full_size(shared, stagger):
     """The whole headline job (32 layers x 32 sequences x 8 KV heads at budget 2048, one shared shuffled pool)
-    stepped 36 times in every mode of the layered driver: the paper's procedure, cached scores, one-launch
+    stepped 36 times in every mode of the layered driver: the paper's procedure, cached scores, one-pass
     score+evict, separate append launches, HIP-graph replay.  Every mode must end with the same block tables,
     lengths and spare counters, bit for bit (the decisions are the same decisions), and the same attention
     outputs within the bf16 tolerance (the fused and the separate attention sum in different orders).  Also in
-    the head-shared layout (which has no one-launch score+evict), and with prompts just under the budget so that
+    the head-shared layout (which has no one-pass score+evict), and with prompts just under the budget so that
     the sequences evict at different steps.  In the first mode one layer of the 32 is stepped by the oracle as
     well: its table, lengths, spare counters and attention outputs are compared at every step, so the other
     modes are compared with a run that is itself checked against the oracle."""

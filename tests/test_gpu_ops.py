@@ -127,7 +127,7 @@ def test_score_blocks_closed_forms():
 @pytest.mark.parametrize("D", [64, 128])
 @pytest.mark.parametrize("B", [16, 32, 64, 128])
 @pytest.mark.parametrize("want_scores", [True, False])
-def test_score_evict_one_launch(dt, D, B, want_scores):
+def test_score_evict_one_pass(dt, D, B, want_scores):
     """pe_score_evict against oracle score_blocks + evict_blocks: odd and even page counts, one page, a partial
     tail (no trigger), under budget (no trigger), an empty row, more rows than waves (Hk = 5)."""
     print("case score_evict", dt, D, B, want_scores, flush=True)
