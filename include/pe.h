@@ -300,6 +300,22 @@ int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const v
                            int32_t n_spare, float softmax_scale, void* out, void* workspace, size_t workspace_bytes,
                            void* stream);
 
+/*
+ * The call above for `num_layers` layers that share one pool, issued from native code in layer order on `stream`
+ * (a host-side loop, nothing more: layer l+1's launch follows layer l's on the stream, as the layers of a model
+ * do).  `desc` describes ONE layer (num_seqs = S).  Per-layer arrays are stacked along their first axis, layers
+ * folded into the sequence dimension: new_k, new_v [layers*S][Hk][D]; q, out [layers*S][Hq][D]; block_table
+ * [layers*S][Hk][max_blocks]; seq_lens, seq_lens_out [layers*S]; freed_phys, spare_used [layers*S][Hk]; spare
+ * [layers*S][Hk][n_spare] (shared layout: the shapes that layout gives, stacked the same way).  The one workspace
+ * (pe_workspace_bytes(PE_OP_APPEND_PAGED_DECODE, desc, 0)) serves every layer.  Returns the first non-OK status;
+ * layers before it have been enqueued.
+ */
+int pe_append_paged_decode_layers(const pe_cache_desc* desc, int32_t num_layers, const void* new_k, const void* new_v,
+                                  const void* q, void* k_pool, void* v_pool, int32_t* block_table,
+                                  const int32_t* seq_lens, int32_t* seq_lens_out, int32_t* freed_phys,
+                                  const int32_t* spare, int32_t* spare_used, int32_t n_spare, float softmax_scale,
+                                  void* out, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

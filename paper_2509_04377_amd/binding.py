@@ -23,7 +23,7 @@ PE_STATIC_SCRATCH_BYTES = 8 * 1024 * 1024
 EXPORTS = ["pe_workspace_bytes", "pe_status_string", "pe_version", "pe_decode_splits",
            "pe_score_blocks", "pe_prefill_prune", "pe_evict_blocks", "pe_paged_decode", "pe_append_kv",
            "pe_append_paged_decode", "pe_score_recent_blocks", "pe_evict_blocks_cached", "pe_evict_blocks_ex", "pe_score_evict",
-           "pe_score_triggered_blocks", "pe_paged_decode_static"]
+           "pe_score_triggered_blocks", "pe_paged_decode_static", "pe_append_paged_decode_layers"]
 
 
 class pe_cache_desc(ctypes.Structure):
@@ -89,6 +89,9 @@ def lib():
         L.pe_append_paged_decode.restype = ctypes.c_int
         L.pe_append_paged_decode.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ctypes.c_float, vp, vp, sz,
                                              vp]
+        L.pe_append_paged_decode_layers.restype = ctypes.c_int
+        L.pe_append_paged_decode_layers.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, ctypes.c_float,
+                                                    vp, vp, sz, vp]
         L.pe_evict_blocks_ex.restype = ctypes.c_int
         L.pe_evict_blocks_ex.argtypes = [dp, ctypes.POINTER(pe_evict_opts), vp, vp, vp, i32, vp, vp, vp]
         L.pe_score_recent_blocks.restype = ctypes.c_int
@@ -305,3 +308,19 @@ def pe_append_paged_decode(desc, new_k, new_v, q, k_pool, v_pool, block_table, s
                                         ptr(spare_used, "spare_used", torch.int32), int(spare.shape[-1]),
                                         ctypes.c_float(softmax_scale), ptr(out, "out"), wp, wn, stream_arg()),
            "pe_append_paged_decode")
+
+
+def pe_append_paged_decode_layers(desc, num_layers, new_k, new_v, q, k_pool, v_pool, block_table, seq_lens, seq_lens_out,
+                                  freed_phys, spare, spare_used, softmax_scale, out, workspace=None):
+    if HostOnly.active:
+        return
+    wp, wn = ws_args(workspace)
+    check(lib().pe_append_paged_decode_layers(ctypes.byref(desc), int(num_layers), ptr(new_k, "new_k"), ptr(new_v, "new_v"),
+                                              ptr(q, "q"), ptr(k_pool, "k_pool"), ptr(v_pool, "v_pool"),
+                                              ptr(block_table, "block_table", torch.int32),
+                                              ptr(seq_lens, "seq_lens", torch.int32),
+                                              ptr(seq_lens_out, "seq_lens_out", torch.int32),
+                                              ptr(freed_phys, "freed_phys", torch.int32), ptr(spare, "spare", torch.int32),
+                                              ptr(spare_used, "spare_used", torch.int32), int(spare.shape[-1]),
+                                              ctypes.c_float(softmax_scale), ptr(out, "out"), wp, wn, stream_arg()),
+          "pe_append_paged_decode_layers")

@@ -474,6 +474,33 @@ int pe_append_paged_decode(const pe_cache_desc* desc, const void* new_k, const v
   return pe::launch_paged_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PE_OK : PE_ERR_HIP;
 }
 
+int pe_append_paged_decode_layers(const pe_cache_desc* desc, int32_t num_layers, const void* new_k, const void* new_v,
+                                  const void* q, void* k_pool, void* v_pool, int32_t* block_table,
+                                  const int32_t* seq_lens, int32_t* seq_lens_out, int32_t* freed_phys,
+                                  const int32_t* spare, int32_t* spare_used, int32_t n_spare, float softmax_scale,
+                                  void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  const int st = check_desc(desc);
+  if (st != PE_OK) return st;
+  if (num_layers < 1 || n_spare < 1) return PE_ERR_INVALID_ARG;
+  if (!new_k || !new_v || !q || !block_table || !seq_lens || !seq_lens_out || !freed_phys || !spare || !spare_used || !out)
+    return PE_ERR_INVALID_ARG;
+  const bool shared = desc->layout == PE_LAYOUT_SHARED;
+  const size_t elem = desc->dtype == PE_BF16 ? 2 : 4;
+  const int64_t S = desc->num_seqs;
+  const int64_t rows = shared ? S : S * desc->num_kv_heads;  // table rows, spare lists, freed pages per layer
+  const size_t kv_bytes = (size_t)S * desc->num_kv_heads * desc->head_dim * elem;
+  const size_t q_bytes = (size_t)S * desc->num_q_heads * desc->head_dim * elem;
+  for (int32_t l = 0; l < num_layers; ++l) {
+    const int rc = pe_append_paged_decode(
+        desc, static_cast<const char*>(new_k) + l * kv_bytes, static_cast<const char*>(new_v) + l * kv_bytes,
+        static_cast<const char*>(q) + l * q_bytes, k_pool, v_pool, block_table + l * rows * desc->max_blocks,
+        seq_lens + l * S, seq_lens_out + l * S, freed_phys + l * rows, spare + l * rows * n_spare, spare_used + l * rows,
+        n_spare, softmax_scale, static_cast<char*>(out) + l * q_bytes, workspace, workspace_bytes, stream);
+    if (rc != PE_OK) return rc;
+  }
+  return PE_OK;
+}
+
 int pe_append_kv(const pe_cache_desc* desc, const void* new_k, const void* new_v, void* k_pool, void* v_pool,
                  int32_t* block_table, int32_t* seq_lens, int32_t* freed_phys, const int32_t* spare,
                  int32_t* spare_used, int32_t n_spare, void* stream) {

@@ -247,6 +247,7 @@ class LayeredCache:
             c.decode_ws = self.decode_ws
             c.seq_lens_alt = f.seq_lens_alt[l * num_seqs:(l + 1) * num_seqs]
         self.fused = True
+        self.native_layers = True   # fused mode: the per-layer launches are issued by one native call
         self.host_lens = [0] * num_seqs   # the same in every layer
 
     def prefill_prune_layer(self, layer, k_in, v_in, cu_seqlens, max_seqlen, kept_idx_out=None, workspace=None):
@@ -265,7 +266,20 @@ class LayeredCache:
             self.folded.host_lens = self.host_lens * self.layers
             self.folded.score_and_evict()
             self.host_lens = [n - self.B if t else n for n, t in zip(self.host_lens, trig)]
-        for l, c in enumerate(self.per_layer):
+        if self.fused and self.native_layers:
+            # one native call issues the fused append + attention launch of every layer, in layer order
+            f = self.folded
+            if layer_hook is not None:
+                layer_hook(0, 0)
+            pe.pe_append_paged_decode_layers(self.per_layer[0].desc, self.layers, new_k, new_v, q, f.k_pool, f.v_pool,
+                                             f.block_table, f.seq_lens, f.seq_lens_alt, f.freed_phys, f.spare,
+                                             f.spare_used, float(self.D) ** -0.5 if softmax_scale is None
+                                             else softmax_scale, out, self.decode_ws)
+            if layer_hook is not None:
+                layer_hook(self.layers - 1, 1)
+            for c in self.per_layer:
+                c.seq_lens, c.seq_lens_alt = c.seq_lens_alt, c.seq_lens
+        for l, c in enumerate(self.per_layer if not (self.fused and self.native_layers) else ()):
             if self.fused:
                 if layer_hook is not None:
                     layer_hook(l, 0)

@@ -327,7 +327,8 @@ def _oracle_layer_state(wl, lens, k_in, v_in, cu, layout, l, shared):
 def test_all_driver_modes_agree_at_full_size(shared, stagger):
     """The whole headline job (32 layers x 32 sequences x 8 KV heads at budget 2048, one shared shuffled pool)
     stepped 36 times in every mode of the layered driver: the paper's procedure, cached scores, one-pass
-    score+evict, separate append launches, HIP-graph replay.  Every mode must end with the same block tables,
+    score+evict, separate append launches, HIP-graph replay, the layers' launches issued by one native call or by one
+    call per layer.  Every mode must end with the same block tables,
     lengths and spare counters, bit for bit (the decisions are the same decisions), and the same attention
     outputs within the bf16 tolerance (the fused and the separate attention sum in different orders).  Also in
     the head-shared layout (which has no one-pass score+evict), and with prompts just under the budget so that
@@ -348,7 +349,7 @@ def test_all_driver_modes_agree_at_full_size(shared, stagger):
     q = torch.randn((4, L, S, Hq, D), generator=g, device=DEV).to(wl.torch_dtype)
     ref = None
     ls = 17          # the layer of the first mode's run that is stepped by the oracle as well
-    for mode in ("paper", "cached", "fused_evict", "unfused", "graph"):
+    for mode in ("paper", "cached", "fused_evict", "unfused", "graph", "python_loop"):
         if shared and mode == "fused_evict":
             continue
         layout = synth.page_layout(wl, lens * L, SEED, steps=steps, shared=shared)
@@ -364,6 +365,7 @@ def test_all_driver_modes_agree_at_full_size(shared, stagger):
         eng.folded.cached_scores = mode == "cached"
         eng.folded.fused_evict = mode == "fused_evict"
         eng.fused = mode != "unfused"
+        eng.native_layers = mode != "python_loop"   # one native call per step, or one C-ABI call per layer
         out = torch.zeros((L, S, Hq, D), dtype=wl.torch_dtype, device=DEV)
         n_trig = 0
         if mode == "graph":
