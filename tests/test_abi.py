@@ -85,6 +85,18 @@ def test_null_pointers_and_bad_budget():
     assert L.pe_score_blocks(ctypes.byref(d), misaligned, FAKE, FAKE, FAKE, FAKE, None, 0, None) == pe.PE_ERR_INVALID_ARG
 
 
+def test_layers_call_host_checks():
+    d = _desc()
+    L = pe.lib()
+    f = ctypes.c_float(0.1)
+    args = lambda n, first=FAKE: (ctypes.byref(d), n, first, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 2, f,
+                                  FAKE, FAKE, 1 << 30, None)
+    assert L.pe_append_paged_decode_layers(*args(0)) == pe.PE_ERR_INVALID_ARG
+    assert L.pe_append_paged_decode_layers(*args(3, None)) == pe.PE_ERR_INVALID_ARG
+    # the per-layer checks apply too: seq_lens_out must not alias seq_lens (both FAKE here)
+    assert L.pe_append_paged_decode_layers(*args(3)) == pe.PE_ERR_INVALID_ARG
+
+
 def test_shared_layout_host_checks():
     d = _desc(layout=pe.PE_LAYOUT_SHARED)
     L = pe.lib()
