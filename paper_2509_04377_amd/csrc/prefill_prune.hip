@@ -28,7 +28,7 @@ constexpr int kWaves = kThreads / kWave;
 constexpr int kChunk = 1024;  // tokens per chunk in the count pass and in the gather (4 per gather thread)
 constexpr int kTokPerThread = kChunk / kThreads;
 constexpr int kSweepLoads = 4;  // token sweep: wave-loads of K (and of V) per step
-constexpr int kSweepIters = 4;  // and steps per wave (8 measured the same)
+constexpr int kSweepIters = 2;  // and steps per wave (4 and 8: the same on 2 GB of prompt, 5 us slower on 1 GB: longer tail)
 
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
