@@ -127,22 +127,6 @@ def check(status, where):
         raise PeError(status, where)
 
 
-class HostOnly:
-    """While active, the kernel-launching wrappers below return without calling the library, so a driver can
-    advance its host-side bookkeeping for a step whose launches are replayed from a captured HIP graph."""
-    active = False
-
-    def __enter__(self):
-        HostOnly.active = True
-
-    def __exit__(self, *exc):
-        HostOnly.active = False
-
-
-def host_only():
-    return HostOnly()
-
-
 def ptr(t, name, dtype=None, optional=False):
     if t is None:
         if optional:
@@ -180,8 +164,6 @@ def alloc_workspace(op: int, desc: pe_cache_desc, total_tokens: int = 0, device=
 
 
 def pe_score_blocks(desc, k_pool, v_pool, block_table, seq_lens, scores_out, workspace=None):
-    if HostOnly.active:
-        return
     wp, wn = ws_args(workspace)
     check(lib().pe_score_blocks(ctypes.byref(desc), ptr(k_pool, "k_pool"), ptr(v_pool, "v_pool"),
                                  ptr(block_table, "block_table", torch.int32), ptr(seq_lens, "seq_lens", torch.int32),
@@ -190,8 +172,6 @@ def pe_score_blocks(desc, k_pool, v_pool, block_table, seq_lens, scores_out, wor
 
 def pe_prefill_prune(desc, k_in, v_in, cu_seqlens, total_tokens, max_seqlen, budget_tokens, k_pool, v_pool,
                      block_table, seq_lens_out, kept_idx_out, workspace):
-    if HostOnly.active:
-        return
     wp, wn = ws_args(workspace)
     check(lib().pe_prefill_prune(ctypes.byref(desc), ptr(k_in, "k_in"), ptr(v_in, "v_in"),
                                   ptr(cu_seqlens, "cu_seqlens", torch.int32), int(total_tokens), int(max_seqlen),
@@ -203,8 +183,6 @@ def pe_prefill_prune(desc, k_in, v_in, cu_seqlens, total_tokens, max_seqlen, bud
 
 
 def pe_evict_blocks(desc, scores, block_table, seq_lens, budget_tokens, evicted_logical_out, freed_phys_out):
-    if HostOnly.active:
-        return
     check(lib().pe_evict_blocks(ctypes.byref(desc), ptr(scores, "scores", torch.float32),
                                  ptr(block_table, "block_table", torch.int32), ptr(seq_lens, "seq_lens", torch.int32),
                                  int(budget_tokens), ptr(evicted_logical_out, "evicted_logical_out", torch.int32),
@@ -212,8 +190,6 @@ def pe_evict_blocks(desc, scores, block_table, seq_lens, budget_tokens, evicted_
 
 
 def pe_score_triggered_blocks(desc, k_pool, v_pool, block_table, seq_lens, budget_tokens, scores_inout):
-    if HostOnly.active:
-        return
     check(lib().pe_score_triggered_blocks(ctypes.byref(desc), ptr(k_pool, "k_pool"), ptr(v_pool, "v_pool"),
                                            ptr(block_table, "block_table", torch.int32),
                                            ptr(seq_lens, "seq_lens", torch.int32), int(budget_tokens),
@@ -223,8 +199,6 @@ def pe_score_triggered_blocks(desc, k_pool, v_pool, block_table, seq_lens, budge
 
 def pe_score_evict(desc, k_pool, v_pool, block_table, seq_lens, budget_tokens, scores_out, evicted_logical_out,
                    freed_phys_out):
-    if HostOnly.active:
-        return
     check(lib().pe_score_evict(ctypes.byref(desc), ptr(k_pool, "k_pool"), ptr(v_pool, "v_pool"),
                                 ptr(block_table, "block_table", torch.int32), ptr(seq_lens, "seq_lens", torch.int32),
                                 int(budget_tokens), ptr(scores_out, "scores_out", torch.float32, optional=True),
@@ -233,8 +207,6 @@ def pe_score_evict(desc, k_pool, v_pool, block_table, seq_lens, budget_tokens, s
 
 
 def pe_score_recent_blocks(desc, k_pool, v_pool, block_table, seq_lens, recent, scores_inout):
-    if HostOnly.active:
-        return
     check(lib().pe_score_recent_blocks(ctypes.byref(desc), ptr(k_pool, "k_pool"), ptr(v_pool, "v_pool"),
                                         ptr(block_table, "block_table", torch.int32),
                                         ptr(seq_lens, "seq_lens", torch.int32), int(recent),
@@ -244,8 +216,6 @@ def pe_score_recent_blocks(desc, k_pool, v_pool, block_table, seq_lens, recent, 
 
 def pe_evict_blocks_cached(desc, scores_inout, block_table, seq_lens, budget_tokens, evicted_logical_out,
                            freed_phys_out):
-    if HostOnly.active:
-        return
     check(lib().pe_evict_blocks_cached(ctypes.byref(desc), ptr(scores_inout, "scores_inout", torch.float32),
                                         ptr(block_table, "block_table", torch.int32),
                                         ptr(seq_lens, "seq_lens", torch.int32), int(budget_tokens),
@@ -255,8 +225,6 @@ def pe_evict_blocks_cached(desc, scores_inout, block_table, seq_lens, budget_tok
 
 
 def pe_evict_blocks_ex(desc, opts, scores, block_table, seq_lens, budget_tokens, evicted_logical_out, freed_phys_out):
-    if HostOnly.active:
-        return
     check(lib().pe_evict_blocks_ex(ctypes.byref(desc), ctypes.byref(opts),
                                     ptr(scores, "scores", torch.float32, optional=True),
                                     ptr(block_table, "block_table", torch.int32),
@@ -267,8 +235,6 @@ def pe_evict_blocks_ex(desc, opts, scores, block_table, seq_lens, budget_tokens,
 
 
 def pe_paged_decode(desc, q, k_pool, v_pool, block_table, seq_lens, softmax_scale, out, workspace=None):
-    if HostOnly.active:
-        return
     wp, wn = ws_args(workspace)
     check(lib().pe_paged_decode(ctypes.byref(desc), ptr(q, "q"), ptr(k_pool, "k_pool"), ptr(v_pool, "v_pool"),
                                  ptr(block_table, "block_table", torch.int32), ptr(seq_lens, "seq_lens", torch.int32),
@@ -276,8 +242,6 @@ def pe_paged_decode(desc, q, k_pool, v_pool, block_table, seq_lens, softmax_scal
 
 
 def pe_paged_decode_static(desc, q, k_pool, v_pool, block_table, seq_lens, softmax_scale, out):
-    if HostOnly.active:
-        return
     check(lib().pe_paged_decode_static(ctypes.byref(desc), ptr(q, "q"), ptr(k_pool, "k_pool"), ptr(v_pool, "v_pool"),
                                        ptr(block_table, "block_table", torch.int32),
                                        ptr(seq_lens, "seq_lens", torch.int32), ctypes.c_float(softmax_scale),
@@ -285,8 +249,6 @@ def pe_paged_decode_static(desc, q, k_pool, v_pool, block_table, seq_lens, softm
 
 
 def pe_append_kv(desc, new_k, new_v, k_pool, v_pool, block_table, seq_lens, freed_phys, spare, spare_used):
-    if HostOnly.active:
-        return
     check(lib().pe_append_kv(ctypes.byref(desc), ptr(new_k, "new_k"), ptr(new_v, "new_v"), ptr(k_pool, "k_pool"),
                               ptr(v_pool, "v_pool"), ptr(block_table, "block_table", torch.int32),
                               ptr(seq_lens, "seq_lens", torch.int32), ptr(freed_phys, "freed_phys", torch.int32),
@@ -296,8 +258,6 @@ def pe_append_kv(desc, new_k, new_v, k_pool, v_pool, block_table, seq_lens, free
 
 def pe_append_paged_decode(desc, new_k, new_v, q, k_pool, v_pool, block_table, seq_lens, seq_lens_out, freed_phys, spare,
                            spare_used, softmax_scale, out, workspace=None):
-    if HostOnly.active:
-        return
     wp, wn = ws_args(workspace)
     check(lib().pe_append_paged_decode(ctypes.byref(desc), ptr(new_k, "new_k"), ptr(new_v, "new_v"), ptr(q, "q"),
                                         ptr(k_pool, "k_pool"), ptr(v_pool, "v_pool"),
@@ -312,8 +272,6 @@ def pe_append_paged_decode(desc, new_k, new_v, q, k_pool, v_pool, block_table, s
 
 def pe_append_paged_decode_layers(desc, num_layers, new_k, new_v, q, k_pool, v_pool, block_table, seq_lens, seq_lens_out,
                                   freed_phys, spare, spare_used, softmax_scale, out, workspace=None):
-    if HostOnly.active:
-        return
     wp, wn = ws_args(workspace)
     check(lib().pe_append_paged_decode_layers(ctypes.byref(desc), int(num_layers), ptr(new_k, "new_k"), ptr(new_v, "new_v"),
                                               ptr(q, "q"), ptr(k_pool, "k_pool"), ptr(v_pool, "v_pool"),

@@ -21,6 +21,28 @@ import torch
 from . import binding as pe
 
 
+class HostOnly:
+    """While active, the drivers below advance their host-side bookkeeping (length mirror, which lengths array is
+    current) without calling the library: the launches of such a step are replayed from a captured HIP graph."""
+    active = False
+
+    def __enter__(self):
+        HostOnly.active = True
+
+    def __exit__(self, *exc):
+        HostOnly.active = False
+
+
+def host_only():
+    return HostOnly()
+
+
+def _launch(fn, *args):
+    """Call a binding function unless the step's launches come from a graph replay."""
+    if not HostOnly.active:
+        fn(*args)
+
+
 def triggers(host_lens, block_size: int, budget: int) -> List[bool]:
     """Alg. 3's branch per sequence: the newest page has just filled (L % B == 0) and the sequence holds at
     least the budget (with a budget >= context nothing is ever evicted: Sec. 4.3)."""
@@ -92,7 +114,7 @@ class PagedCache:
         total = k_in.shape[0]
         if workspace is None:
             workspace = pe.alloc_workspace(pe.PE_OP_PREFILL_PRUNE, self.desc, total, device=k_in.device)
-        pe.pe_prefill_prune(self.desc, k_in, v_in, cu_seqlens, total, max_seqlen, self.budget, self.k_pool, self.v_pool,
+        _launch(pe.pe_prefill_prune, self.desc, k_in, v_in, cu_seqlens, total, max_seqlen, self.budget, self.k_pool, self.v_pool,
                          self.block_table, self.seq_lens, kept_idx_out, workspace)
 
     def set_host_lens(self, prompt_lens):
@@ -128,7 +150,7 @@ class PagedCache:
             softmax_scale = float(self.desc.head_dim) ** -0.5
         if self.seq_lens_alt is None:
             self.seq_lens_alt = torch.empty_like(self.seq_lens)
-        if not pe.HostOnly.active:
+        if not HostOnly.active:
             i32 = torch.int32
             wp, wn = pe.ws_args(self.decode_ws)
             pe.check(pe.lib().pe_append_paged_decode(
@@ -156,14 +178,14 @@ class PagedCache:
         self.host_lens = [n + 1 for n in self.host_lens]
 
     def score_blocks(self):
-        pe.pe_score_blocks(self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, self.scores)
+        _launch(pe.pe_score_blocks, self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, self.scores)
 
     def score_triggered_blocks(self):
-        pe.pe_score_triggered_blocks(self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, self.budget,
+        _launch(pe.pe_score_triggered_blocks, self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, self.budget,
                                   self.scores)
 
     def evict_blocks(self):
-        pe.pe_evict_blocks(self.desc, self.scores, self.block_table, self.seq_lens, self.budget, self.evicted_logical,
+        _launch(pe.pe_evict_blocks, self.desc, self.scores, self.block_table, self.seq_lens, self.budget, self.evicted_logical,
                         self.freed_phys)
 
     def score_and_evict(self):
@@ -175,11 +197,11 @@ class PagedCache:
             opts = pe.pe_evict_opts(o.policy, o.protect_first, o.protect_last, o.share_heads, 0)
             if o.policy != pe.PE_POLICY_OLDEST:
                 self.score_triggered_blocks()
-            pe.pe_evict_blocks_ex(self.desc, opts, self.scores if o.policy != pe.PE_POLICY_OLDEST else None,
+            _launch(pe.pe_evict_blocks_ex, self.desc, opts, self.scores if o.policy != pe.PE_POLICY_OLDEST else None,
                                self.block_table, self.seq_lens, self.budget, self.evicted_logical, self.freed_phys)
             return
         if self.fused_evict and not self.cached_scores:
-            pe.pe_score_evict(self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, self.budget, None,
+            _launch(pe.pe_score_evict, self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, self.budget, None,
                            self.evicted_logical, self.freed_phys)
             return
         if not self.cached_scores:   # Alg. 3: score the pages of the sequences that evict now, then evict
@@ -192,14 +214,14 @@ class PagedCache:
         else:
             recent = max(f - sc for f, sc in zip(full, self.host_scored))
             if recent > 0:
-                pe.pe_score_recent_blocks(self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, recent,
+                _launch(pe.pe_score_recent_blocks, self.desc, self.k_pool, self.v_pool, self.block_table, self.seq_lens, recent,
                                        self.scores)
-        pe.pe_evict_blocks_cached(self.desc, self.scores, self.block_table, self.seq_lens, self.budget,
+        _launch(pe.pe_evict_blocks_cached, self.desc, self.scores, self.block_table, self.seq_lens, self.budget,
                                self.evicted_logical, self.freed_phys)
         self.host_scored = [f - 1 if t else f for f, t in zip(full, self.triggers())]
 
     def append_kv(self, new_k, new_v):
-        if pe.HostOnly.active:
+        if HostOnly.active:
             return
         i32 = torch.int32
         pe.check(pe.lib().pe_append_kv(ctypes.byref(self.desc), pe.ptr(new_k, "new_k"), pe.ptr(new_v, "new_v"),
@@ -210,7 +232,7 @@ class PagedCache:
     def paged_decode(self, q, out, softmax_scale=None):
         if softmax_scale is None:
             softmax_scale = float(self.desc.head_dim) ** -0.5
-        if pe.HostOnly.active:
+        if HostOnly.active:
             return
         wp, wn = pe.ws_args(self.decode_ws)
         pe.check(pe.lib().pe_paged_decode(ctypes.byref(self.desc), pe.ptr(q, "q"), self._sp("k_pool"), self._sp("v_pool"),
@@ -271,7 +293,7 @@ class LayeredCache:
             f = self.folded
             if layer_hook is not None:
                 layer_hook(0, 0)
-            pe.pe_append_paged_decode_layers(self.per_layer[0].desc, self.layers, new_k, new_v, q, f.k_pool, f.v_pool,
+            _launch(pe.pe_append_paged_decode_layers, self.per_layer[0].desc, self.layers, new_k, new_v, q, f.k_pool, f.v_pool,
                                              f.block_table, f.seq_lens, f.seq_lens_alt, f.freed_phys, f.spare,
                                              f.spare_used, float(self.D) ** -0.5 if softmax_scale is None
                                              else softmax_scale, out, self.decode_ws)
@@ -330,7 +352,7 @@ class GraphedStepper:
                 trig = self.eng.decode_step(*self.args)
             self.graphs[key] = g
         else:
-            with pe.host_only():
+            with host_only():
                 trig = self.eng.decode_step(*self.args)
         g.replay()
         return trig
