@@ -32,6 +32,7 @@
  *     every used table entry lies in [0, num_phys_blocks), rows do not share pages,
  *     seq_lens[s] <= max_blocks*B, and all K/V values are finite.
  *   - Workspaces must be 256-byte aligned.  Calls that share a workspace must be ordered on one stream.
+ *     (pe_paged_decode_static keeps its split partials in a static device array of the library instead.)
  */
 #ifndef PE_H_
 #define PE_H_
